@@ -1,0 +1,418 @@
+"""CPU fp64 oracle for one GPU's MoE expert layer, forward and backward.  TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the benchmark's cpu_baseline leg may import this file.  It shares no code
+with the HIP path and never calls it.  Everything is NumPy float64; `@` (matmul), `argsort(kind="stable")`
+and `bincount` are the only library primitives used as steps.
+
+What it computes is the plain definition of the layer the paper names (Section II-A: expert FFNs, each
+receiving only the tokens routed to it by a learned gating function; notation table in Section III-A: E routed
+experts, E_s shared always-active experts, top-k routing, n_mat = 3 SwiGLU matrices; Section III-A memory
+model: W_up, W_gate in R^{d x f}, W_down in R^{f x d}, per-expert token sets s_e; Section III-B: dispatch
+moves b*s*k rows of d_model values, combine is the reverse).  The paper gives no formula beyond that, so the
+following readings are fixed here:
+
+  * gate: softmax over all E logits, the k largest LOGITS are selected (descending, ties -> lower id),
+    weight = that probability, divided by the sum over the selected ones when `renorm`;
+  * shared experts are extra ids E..E+E_s-1 taken by every token with weight 1, outside the softmax;
+  * FFN_e(v) = ( silu(v W_gate[e]) * (v W_up[e]) ) W_down[e],  silu(z) = z / (1 + exp(-z)), no biases;
+  * dropless: every slot is processed, no capacity, no padding;
+  * the gate weight multiplies the expert output at combine;
+  * permutation = stable counting sort of slot ids s = t*K' + j by expert id.
+
+Backward is the exact derivative of L = sum(out * dout) with respect to x (expert path only), the three
+weight tensors, the gate weights and the logits.
+
+Pins (tests/test_oracle_*.py): pure-Python brute force of every definition on tiny inputs, central finite
+differences of every gradient, torch-CPU float64 autograd on a dense one-hot formulation of the same layer,
+closed forms (renorm sums to 1, equal logits, E=1/k=1 reduces to a dense SwiGLU FFN), bijection / stability
+invariants of the permutation.  The paper prints no worked numbers for this path, so no pin comes from it.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------------------------------------------
+# routing (Section II-A gating; Section III-A symbols E, E_s, k)
+# --------------------------------------------------------------------------------------------------------------
+
+
+def softmax_rows(logits):
+    """Row-wise softmax in float64 with max subtraction."""
+    z = np.asarray(logits, dtype=F64)
+    z = z - z.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def route_topk(logits, k, E_shared=0, renorm=True):
+    """Top-k softmax gating.
+
+    logits [T,E] -> (topk_idx [T,K'] int32, topk_w [T,K'] float64, probs [T,E] float64), K' = k + E_shared.
+    Selection compares logits (exactly), not probabilities: descending logit, equal logits -> lower expert id.
+    """
+    z = np.asarray(logits, dtype=F64)
+    T, E = z.shape
+    assert 1 <= k <= E
+    probs = softmax_rows(z)
+    # stable sort of -logit keeps the original (ascending id) order among equal logits
+    order = np.argsort(-z, axis=1, kind="stable")
+    sel = order[:, :k]
+    w = np.take_along_axis(probs, sel, axis=1)
+    if renorm:
+        w = w / w.sum(axis=1, keepdims=True)
+    idx = np.empty((T, k + E_shared), dtype=np.int32)
+    wt = np.empty((T, k + E_shared), dtype=F64)
+    idx[:, :k] = sel
+    wt[:, :k] = w
+    for j in range(E_shared):
+        idx[:, k + j] = E + j
+        wt[:, k + j] = 1.0
+    return idx, wt, probs
+
+
+def route_topk_bwd(dtopk_w, topk_idx, topk_w, probs, k, renorm=True):
+    """Gradient of the gate weights with respect to the logits.
+
+    renorm: the k weights are a softmax over the selected logits, so for selected j
+            dlogit[sel_j] = w_j (dw_j - sum_i w_i dw_i) and 0 elsewhere.
+    no renorm: w_j = p_{sel_j}, so dlogit[m] = p_m ( [m selected] dw_m - sum_j p_{sel_j} dw_j ) for every m.
+    Shared slots (j >= k) carry constant weight 1 and contribute nothing.
+    """
+    dw = np.asarray(dtopk_w, dtype=F64)[:, :k]
+    idx = np.asarray(topk_idx)[:, :k].astype(np.int64)
+    w = np.asarray(topk_w, dtype=F64)[:, :k]
+    p = np.asarray(probs, dtype=F64)
+    T, E = p.shape
+    dlogits = np.zeros((T, E), dtype=F64)
+    rows = np.arange(T)[:, None]
+    if renorm:
+        inner = (w * dw).sum(axis=1, keepdims=True)
+        dlogits[rows, idx] = w * (dw - inner)
+    else:
+        psel = p[rows, idx]
+        inner = (psel * dw).sum(axis=1, keepdims=True)
+        dlogits = -p * inner
+        dlogits[rows, idx] += psel * dw
+    return dlogits
+
+
+# --------------------------------------------------------------------------------------------------------------
+# permutation artefacts (local pack before the dispatch of Section III-B)
+# --------------------------------------------------------------------------------------------------------------
+
+
+def permute_maps(topk_idx, n_experts):
+    """Stable counting sort of the slots s = t*K' + j by expert id.
+
+    Returns counts [E'], offsets [E'+1] (exclusive prefix sum, offsets[E'] = N), row_of_slot [N],
+    slot_of_row [N], all int32."""
+    flat = np.asarray(topk_idx).reshape(-1).astype(np.int64)
+    N = flat.size
+    assert flat.size == 0 or (flat.min() >= 0 and flat.max() < n_experts)
+    counts = np.bincount(flat, minlength=n_experts).astype(np.int32)
+    offsets = np.zeros(n_experts + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    slot_of_row = np.argsort(flat, kind="stable").astype(np.int32)
+    row_of_slot = np.empty(N, dtype=np.int32)
+    row_of_slot[slot_of_row] = np.arange(N, dtype=np.int32)
+    return counts, offsets, row_of_slot, slot_of_row
+
+
+def permute_rows(x, slot_of_row, K_slots):
+    """x_perm[r] = x[slot_of_row[r] // K'] (a copy of rows; works on any dtype, e.g. raw bf16 bit patterns)."""
+    x = np.asarray(x)
+    return x[np.asarray(slot_of_row, dtype=np.int64) // K_slots]
+
+
+def permute_bwd(dx_perm, row_of_slot, K_slots):
+    """dx[t] = sum_j dx_perm[row_of_slot[t*K'+j]] (the derivative of the row copy)."""
+    g = np.asarray(dx_perm, dtype=F64)
+    ros = np.asarray(row_of_slot, dtype=np.int64).reshape(-1, K_slots)
+    return g[ros].sum(axis=1)
+
+
+# --------------------------------------------------------------------------------------------------------------
+# expert FFN (Section III-A: three matrices per expert, SwiGLU)
+# --------------------------------------------------------------------------------------------------------------
+
+
+def silu(z):
+    return z / (1.0 + np.exp(-z))
+
+
+def silu_grad(z):
+    s = 1.0 / (1.0 + np.exp(-z))
+    return s * (1.0 + z * (1.0 - s))
+
+
+def expert_ffn(v, w_gate, w_up, w_down):
+    """FFN(v) = (silu(v Wg) * (v Wu)) Wd for rows v [n,d]; Wg, Wu [d,f]; Wd [f,d].  Returns (Y, G, U, H)."""
+    v = np.asarray(v, dtype=F64)
+    Wg = np.asarray(w_gate, dtype=F64)
+    Wu = np.asarray(w_up, dtype=F64)
+    Wd = np.asarray(w_down, dtype=F64)
+    G = v @ Wg
+    U = v @ Wu
+    H = silu(G) * U
+    return H @ Wd, G, U, H
+
+
+def expert_of_rows(offsets):
+    """Expert id of every permuted row, from the offsets array."""
+    offsets = np.asarray(offsets, dtype=np.int64)
+    return np.repeat(np.arange(offsets.size - 1), np.diff(offsets))
+
+
+def grouped_ffn_fwd(x_perm, offsets, w_gate, w_up, w_down, rows=None):
+    """Y[r] = FFN_{e(r)}(x_perm[r]) where e(r) is the expert whose segment [offsets[e], offsets[e+1]) holds r.
+
+    rows: optional sorted array of row ids to evaluate (slice mode); default all rows.
+    Returns (Y, G, U) for the evaluated rows, in the order of `rows`."""
+    xp = np.asarray(x_perm)
+    offsets = np.asarray(offsets, dtype=np.int64)
+    eor = expert_of_rows(offsets)
+    rows = np.arange(xp.shape[0]) if rows is None else np.asarray(rows, dtype=np.int64)
+    d = xp.shape[1]
+    f = np.asarray(w_gate).shape[2]
+    Y = np.zeros((rows.size, d), dtype=F64)
+    G = np.zeros((rows.size, f), dtype=F64)
+    U = np.zeros((rows.size, f), dtype=F64)
+    for e in np.unique(eor[rows]):
+        m = np.nonzero(eor[rows] == e)[0]
+        y, g, u, _ = expert_ffn(xp[rows[m]], w_gate[e], w_up[e], w_down[e])
+        Y[m], G[m], U[m] = y, g, u
+    return Y, G, U
+
+
+def grouped_ffn_bwd(dy_perm, x_perm, offsets, w_gate, w_up, w_down, rows=None, f_cols=None):
+    """Backward of grouped_ffn_fwd for upstream gradient dy_perm [N,d].
+
+    Per expert e over its rows: dH = dY Wd^T; dWd = H^T dY; dG = dH * U * silu'(G); dU = dH * silu(G);
+    dWg = X^T dG; dWu = X^T dU; dX = dG Wg^T + dU Wu^T.  Experts without rows get dW = 0.
+
+    Slice mode: `rows` restricts dX to those rows (needs the full f of those rows only); `f_cols` restricts the
+    weight gradients to those f-indices: dWg[:, :, f_cols], dWu[:, :, f_cols], dWd[:, f_cols, :] (column j of
+    dWg needs G, U, dH in column j only, over all rows of the expert).
+    Returns (dX [len(rows), d] or None if rows is an empty list, dWg, dWu, dWd) -- the dW are None when
+    f_cols is an empty list."""
+    xp = np.asarray(x_perm)
+    dyp = np.asarray(dy_perm)
+    offsets = np.asarray(offsets, dtype=np.int64)
+    Et = offsets.size - 1
+    N, d = xp.shape
+    f = np.asarray(w_gate).shape[2]
+    eor = expert_of_rows(offsets)
+
+    dX = None
+    want_rows = np.arange(N) if rows is None else np.asarray(rows, dtype=np.int64)
+    if want_rows.size:
+        dX = np.zeros((want_rows.size, d), dtype=F64)
+        for e in np.unique(eor[want_rows]):
+            m = np.nonzero(eor[want_rows] == e)[0]
+            Wg = np.asarray(w_gate[e], dtype=F64)
+            Wu = np.asarray(w_up[e], dtype=F64)
+            Wd = np.asarray(w_down[e], dtype=F64)
+            X = np.asarray(xp[want_rows[m]], dtype=F64)
+            dY = np.asarray(dyp[want_rows[m]], dtype=F64)
+            G = X @ Wg
+            U = X @ Wu
+            dH = dY @ Wd.T
+            dG = dH * U * silu_grad(G)
+            dU = dH * silu(G)
+            dX[m] = dG @ Wg.T + dU @ Wu.T
+
+    dWg = dWu = dWd = None
+    cols = np.arange(f) if f_cols is None else np.asarray(f_cols, dtype=np.int64)
+    if cols.size:
+        dWg = np.zeros((Et, d, cols.size), dtype=F64)
+        dWu = np.zeros((Et, d, cols.size), dtype=F64)
+        dWd = np.zeros((Et, cols.size, d), dtype=F64)
+        for e in range(Et):
+            lo, hi = offsets[e], offsets[e + 1]
+            if hi == lo:
+                continue
+            X = np.asarray(xp[lo:hi], dtype=F64)
+            dY = np.asarray(dyp[lo:hi], dtype=F64)
+            Wg = np.asarray(np.asarray(w_gate[e])[:, cols], dtype=F64)
+            Wu = np.asarray(np.asarray(w_up[e])[:, cols], dtype=F64)
+            Wd = np.asarray(np.asarray(w_down[e])[cols, :], dtype=F64)
+            G = X @ Wg
+            U = X @ Wu
+            H = silu(G) * U
+            dH = dY @ Wd.T
+            dG = dH * U * silu_grad(G)
+            dU = dH * silu(G)
+            dWg[e] = X.T @ dG
+            dWu[e] = X.T @ dU
+            dWd[e] = H.T @ dY
+    return dX, dWg, dWu, dWd
+
+
+# --------------------------------------------------------------------------------------------------------------
+# combine (local unpack after the combine of Section III-B)
+# --------------------------------------------------------------------------------------------------------------
+
+
+def unpermute_combine(y_perm, row_of_slot, topk_w):
+    """out[t] = sum_j w[t,j] * y_perm[row_of_slot[t*K'+j]]."""
+    y = np.asarray(y_perm, dtype=F64)
+    w = np.asarray(topk_w, dtype=F64)
+    ros = np.asarray(row_of_slot, dtype=np.int64).reshape(w.shape)
+    return (w[:, :, None] * y[ros]).sum(axis=1)
+
+
+def unpermute_combine_bwd(dout, y_perm, row_of_slot, topk_w):
+    """dy_perm[row_of_slot[s]] = w[s] * dout[t(s)];  dtopk_w[t,j] = <dout[t], y_perm[row_of_slot[t*K'+j]]>."""
+    g = np.asarray(dout, dtype=F64)
+    y = np.asarray(y_perm, dtype=F64)
+    w = np.asarray(topk_w, dtype=F64)
+    ros = np.asarray(row_of_slot, dtype=np.int64).reshape(w.shape)
+    dy = np.zeros_like(y)
+    dy[ros] = w[:, :, None] * g[:, None, :]
+    dw = (g[:, None, :] * y[ros]).sum(axis=2)
+    return dy, dw
+
+
+# --------------------------------------------------------------------------------------------------------------
+# the whole layer, by its per-token definition (no permutation anywhere)
+# --------------------------------------------------------------------------------------------------------------
+
+
+def layer_forward(x, topk_idx, topk_w, w_gate, w_up, w_down, tokens=None):
+    """out[t] = sum_{j<K'} w[t,j] * FFN_{idx[t,j]}(x[t]), evaluated per token (grouped by expert only to batch
+    the matmuls; no row is moved).  tokens: optional array of token ids (slice mode).
+    Returns (out [len(tokens), d], ffn_out [len(tokens), K', d]) -- ffn_out[i,j] = FFN_{idx[t,j]}(x[t])."""
+    x = np.asarray(x)
+    idx = np.asarray(topk_idx).astype(np.int64)
+    w = np.asarray(topk_w, dtype=F64)
+    tokens = np.arange(x.shape[0]) if tokens is None else np.asarray(tokens, dtype=np.int64)
+    Kp = idx.shape[1]
+    d = x.shape[1]
+    ffn_out = np.zeros((tokens.size, Kp, d), dtype=F64)
+    sub_idx = idx[tokens]
+    for e in np.unique(sub_idx):
+        ti, ji = np.nonzero(sub_idx == e)
+        y, _, _, _ = expert_ffn(x[tokens[ti]], w_gate[e], w_up[e], w_down[e])
+        ffn_out[ti, ji] = y
+    out = (w[tokens][:, :, None] * ffn_out).sum(axis=1)
+    return out, ffn_out
+
+
+def layer_backward(x, topk_idx, topk_w, w_gate, w_up, w_down, dout, tokens=None, f_cols=None):
+    """Gradients of L = sum(out * dout) by the per-token definition.
+
+    For slot (t,j) with expert e: y = FFN_e(x[t]); dtopk_w[t,j] = <dout[t], y>; the slot's upstream gradient is
+    dy = w[t,j] dout[t]; dx[t] += dG Wg^T + dU Wu^T; dW*[e] += the slot's outer products.
+    tokens restricts dx / dtopk_w to those tokens; f_cols restricts dWg/dWu to those columns and dWd to those
+    rows (every token still contributes to the dW).  Pass an empty list to skip either part.
+    Returns dict(dx, dtopk_w, dw_gate, dw_up, dw_down)."""
+    x = np.asarray(x)
+    idx = np.asarray(topk_idx).astype(np.int64)
+    w = np.asarray(topk_w, dtype=F64)
+    g = np.asarray(dout)
+    T, d = x.shape
+    Kp = idx.shape[1]
+    Et = np.asarray(w_gate).shape[0]
+    f = np.asarray(w_gate).shape[2]
+    res = {"dx": None, "dtopk_w": None, "dw_gate": None, "dw_up": None, "dw_down": None}
+
+    toks = np.arange(T) if tokens is None else np.asarray(tokens, dtype=np.int64)
+    if toks.size:
+        dx = np.zeros((toks.size, d), dtype=F64)
+        dw = np.zeros((toks.size, Kp), dtype=F64)
+        sub_idx = idx[toks]
+        for e in np.unique(sub_idx):
+            ti, ji = np.nonzero(sub_idx == e)
+            Wg = np.asarray(w_gate[e], dtype=F64)
+            Wu = np.asarray(w_up[e], dtype=F64)
+            Wd = np.asarray(w_down[e], dtype=F64)
+            X = np.asarray(x[toks[ti]], dtype=F64)
+            D = np.asarray(g[toks[ti]], dtype=F64)
+            G = X @ Wg
+            U = X @ Wu
+            H = silu(G) * U
+            Y = H @ Wd
+            dw[ti, ji] = (D * Y).sum(axis=1)
+            dY = w[toks[ti], ji][:, None] * D
+            dH = dY @ Wd.T
+            dG = dH * U * silu_grad(G)
+            dU = dH * silu(G)
+            np.add.at(dx, ti, dG @ Wg.T + dU @ Wu.T)
+        res["dx"], res["dtopk_w"] = dx, dw
+
+    cols = np.arange(f) if f_cols is None else np.asarray(f_cols, dtype=np.int64)
+    if cols.size:
+        dWg = np.zeros((Et, d, cols.size), dtype=F64)
+        dWu = np.zeros((Et, d, cols.size), dtype=F64)
+        dWd = np.zeros((Et, cols.size, d), dtype=F64)
+        for e in range(Et):
+            ti, ji = np.nonzero(idx == e)
+            if ti.size == 0:
+                continue
+            Wg = np.asarray(np.asarray(w_gate[e])[:, cols], dtype=F64)
+            Wu = np.asarray(np.asarray(w_up[e])[:, cols], dtype=F64)
+            Wd = np.asarray(np.asarray(w_down[e])[cols, :], dtype=F64)
+            X = np.asarray(x[ti], dtype=F64)
+            dY = w[ti, ji][:, None] * np.asarray(g[ti], dtype=F64)
+            G = X @ Wg
+            U = X @ Wu
+            H = silu(G) * U
+            dH = dY @ Wd.T
+            dG = dH * U * silu_grad(G)
+            dU = dH * silu(G)
+            dWg[e] = X.T @ dG
+            dWu[e] = X.T @ dU
+            dWd[e] = H.T @ dY
+        res["dw_gate"], res["dw_up"], res["dw_down"] = dWg, dWu, dWd
+    return res
+
+
+def layer_forward_staged(x, topk_idx, topk_w, w_gate, w_up, w_down, n_experts):
+    """The same forward as layer_forward, but through the stages the C-ABI exposes (permute -> grouped FFN ->
+    combine).  Used by the tests to pin the stage functions to the per-token definition."""
+    Kp = np.asarray(topk_idx).shape[1]
+    counts, offsets, ros, sor = permute_maps(topk_idx, n_experts)
+    xp = permute_rows(np.asarray(x, dtype=F64), sor, Kp)
+    Y, _, _ = grouped_ffn_fwd(xp, offsets, w_gate, w_up, w_down)
+    return unpermute_combine(Y, ros, topk_w)
+
+
+def layer_backward_staged(x, topk_idx, topk_w, w_gate, w_up, w_down, dout, n_experts):
+    """Backward through the C-ABI's stages: combine_bwd -> grouped FFN bwd -> permute_bwd."""
+    Kp = np.asarray(topk_idx).shape[1]
+    counts, offsets, ros, sor = permute_maps(topk_idx, n_experts)
+    xp = permute_rows(np.asarray(x, dtype=F64), sor, Kp)
+    Y, _, _ = grouped_ffn_fwd(xp, offsets, w_gate, w_up, w_down)
+    dY, dw = unpermute_combine_bwd(dout, Y, ros, topk_w)
+    dXp, dWg, dWu, dWd = grouped_ffn_bwd(dY, xp, offsets, w_gate, w_up, w_down)
+    dx = permute_bwd(dXp, ros, Kp)
+    return {"dx": dx, "dtopk_w": dw, "dw_gate": dWg, "dw_up": dWu, "dw_down": dWd}
+
+
+# --------------------------------------------------------------------------------------------------------------
+# error measures used by the parity tests (definitions only; thresholds live in the tests)
+# --------------------------------------------------------------------------------------------------------------
+
+
+def rel_to_max_error(got, ref):
+    """max_i |got_i - ref_i| / max_i |ref_i|  (0 when both are all-zero)."""
+    got = np.asarray(got, dtype=F64)
+    ref = np.asarray(ref, dtype=F64)
+    den = np.abs(ref).max() if ref.size else 0.0
+    num = np.abs(got - ref).max() if ref.size else 0.0
+    if den == 0.0:
+        return 0.0 if num == 0.0 else np.inf
+    return num / den
+
+
+def elementwise_excess(got, ref, rtol):
+    """max_i ( |got_i - ref_i| - rtol*|ref_i| - rtol*rms(ref) ); <= 0 means every element is within bound."""
+    got = np.asarray(got, dtype=F64)
+    ref = np.asarray(ref, dtype=F64)
+    if ref.size == 0:
+        return 0.0
+    rms = np.sqrt(np.mean(ref * ref))
+    return float((np.abs(got - ref) - rtol * np.abs(ref) - rtol * rms).max())
