@@ -1,0 +1,149 @@
+/*
+ * moe.h -- C ABI of the MI355X (gfx950) MoE expert layer: one GPU's share of a Mixture-of-Experts layer,
+ * forward and backward.
+ *
+ * The layer is the one the paper names in Section II-A (expert FFNs, each receiving only the tokens routed to
+ * it by a learned gating function) with the symbols of its notation table (Section III-A: d = d_model,
+ * E routed experts, E_s shared always-active experts, top-k routing, n_mat = 3 SwiGLU matrices, expert FFN
+ * dimension d_ffn) and the weight shapes of its memory model (Section III-A: W_up, W_gate in R^{d x d_ffn},
+ * W_down in R^{d_ffn x d}).  The flow is the per-layer flow of Section IV with the two all-to-alls removed
+ * (one GPU, every expert local):  routing -> local pack -> expert -> local unpack + weighted combine.
+ *
+ * Derived sizes used below:  E' = E + E_shared expert ids,  K' = k + E_shared slots per token,
+ * N = T * K' rows after the permutation, slot id s = t*K' + j.
+ *
+ * Conventions for every compute entry point
+ *   - Every pointer except `const moe_shape*` is a DEVICE pointer owned by the caller.  bf16 tensors travel as
+ *     uint16_t bit patterns.  All tensors are dense, row-major, and 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue work on it:
+ *     they never allocate, free, or synchronise the host.  Scratch comes from the caller's workspace `ws`
+ *     (at least moe_workspace_bytes(shape) bytes, 256-byte aligned); calls that share a workspace must be
+ *     ordered on one stream.
+ *   - Return value: a moe_status.  Argument checks (NULL pointers, shape limits, alignment, workspace size)
+ *     run on the host before anything is launched; on any error nothing is enqueued and no output is touched.
+ *   - Outputs are fully overwritten, except the weight gradients when `accumulate` is 1.
+ *
+ * Shape limits:  1 <= k <= E <= 1024,  E' <= 1024,  T >= 0 (T = 0 is a no-op returning MOE_OK),
+ * T*K' < 2^31,  d_model and d_ffn positive multiples of 64.
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Problem statement of one layer (Section III-A notation).  renorm != 0: the k gate weights of a token are
+ * divided by their sum. */
+typedef struct {
+  int32_t T;        /* tokens on this GPU (b*s of the paper, or incoming rows of an expert-parallel shard) */
+  int32_t d_model;  /* d */
+  int32_t d_ffn;    /* expert FFN intermediate dimension */
+  int32_t E;        /* routed experts held by this GPU */
+  int32_t k;        /* top-k */
+  int32_t E_shared; /* shared (always-active) experts, ids E .. E+E_shared-1 */
+  int32_t renorm;
+} moe_shape;
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_NULL = -1,      /* a required pointer is NULL */
+  MOE_ERR_SHAPE = -2,     /* shape outside the limits above */
+  MOE_ERR_ALIGN = -3,     /* a pointer is not 16-byte aligned (workspace: 256) */
+  MOE_ERR_WORKSPACE = -4, /* workspace smaller than moe_workspace_bytes() */
+  MOE_ERR_RUNTIME = -5    /* a HIP launch failed; hipGetLastError() holds the cause */
+} moe_status;
+
+/* Host-only helpers. */
+const char* moe_status_str(int status);
+/* Bytes of scratch that any single call below may need for this shape (0 if the shape is invalid). */
+size_t moe_workspace_bytes(const moe_shape* shape);
+/* Library version, for the binding's sanity check. */
+int moe_abi_version(void);
+
+/* Top-k softmax gating (Section II-A "learned gating function"; Section III-A symbols E, E_s, k).
+ * Per token: p = softmax(logits[t, 0:E]) in fp32; the k largest LOGITS are selected (descending; equal
+ * logits -> lower expert id first); topk_w[t,j] = p[idx], divided by the sum over the k selected when renorm.
+ * Slots j = k..K'-1 are the shared experts: idx = E + (j-k), weight 1.
+ *   logits     [T,E]  fp32  in
+ *   topk_idx   [T,K'] int32 out
+ *   topk_w     [T,K'] fp32  out
+ *   probs_save [T,E]  fp32  out, may be NULL (needed by moe_route_topk_bwd when renorm == 0)
+ * NaN logits give unspecified (but in-range) indices. */
+int moe_route_topk(const moe_shape* shape, const float* logits, int32_t* topk_idx, float* topk_w,
+                   float* probs_save, void* stream);
+
+/* Derivative of the gate weights with respect to the logits (shared slots contribute nothing).
+ * renorm: dlogits[t, idx_j] = w_j (dw_j - sum_i w_i dw_i), zero elsewhere.
+ * else  : dlogits[t, m] = p_m ([m selected] dw_m - sum_j p_{idx_j} dw_j); probs_save must be non-NULL.
+ *   dtopk_w [T,K'] fp32 in;  topk_idx, topk_w as produced by moe_route_topk;  dlogits [T,E] fp32 out. */
+int moe_route_topk_bwd(const moe_shape* shape, const float* dtopk_w, const int32_t* topk_idx,
+                       const float* topk_w, const float* probs_save, float* dlogits, void* stream);
+
+/* Local pack (the per-GPU half of the dispatch of Section III-B: b*s*k rows of d_model bf16 values grouped by
+ * expert).  A stable counting sort of the slots by expert id:
+ *   counts[e]      = number of slots routed to e                                   [E']   int32 out
+ *   offsets        = exclusive prefix sum of counts, offsets[E'] = N               [E'+1] int32 out
+ *   row_of_slot[s] = offsets[e] + #{s' < s : idx[s'] = e}  (e = idx[s])            [N]    int32 out
+ *   slot_of_row    = inverse of row_of_slot                                        [N]    int32 out
+ *   x_perm[r]      = x[slot_of_row[r] / K']  (bit copy)                            [N,d]  bf16  out
+ * x [T,d] bf16 in; topk_idx [T,K'] int32 in, every id must lie in [0,E') (ids outside are a caller error;
+ * they are clamped into range so that no access leaves the buffers, and the result is then unspecified).
+ * The result is deterministic (no atomics decide an order).  x and x_perm may be NULL together to build the
+ * maps only. */
+int moe_permute(const moe_shape* shape, const uint16_t* x, const int32_t* topk_idx, uint16_t* x_perm,
+                int32_t* counts, int32_t* offsets, int32_t* row_of_slot, int32_t* slot_of_row,
+                void* ws, size_t ws_bytes, void* stream);
+
+/* Derivative of the row copy: dx[t] = sum_j dx_perm[row_of_slot[t*K'+j]] (fp32 sum in slot order, one bf16
+ * rounding).   dx_perm [N,d] bf16 in;  dx [T,d] bf16 out. */
+int moe_permute_bwd(const moe_shape* shape, const uint16_t* dx_perm, const int32_t* row_of_slot,
+                    uint16_t* dx, void* stream);
+
+/* Expert FFNs over the ragged per-expert row segments (Section III-A: three matrices per expert, SwiGLU;
+ * per-expert token counts s_e).  For expert e over rows [offsets[e], offsets[e+1]):
+ *   G = X W_gate[e],  U = X W_up[e],  H = silu(G) * U,  Y = H W_down[e],   silu(z) = z / (1 + exp(-z)).
+ * bf16 operands, fp32 accumulation; G, U, H, Y are each rounded to bf16 once.
+ *   x_perm [N,d] bf16 in;  offsets [E'+1] int32 in (device; never read by the host)
+ *   w_gate, w_up [E',d,f] bf16 in;  w_down [E',f,d] bf16 in
+ *   y_perm [N,d] bf16 out;  save_g, save_u [N,f] bf16 out (the activations backward needs; together with
+ *   x_perm this is the 3*d_ffn + d_model values per row of the paper's activation-memory model)
+ * Experts with no rows cost nothing and touch nothing. */
+int moe_grouped_ffn_fwd(const moe_shape* shape, const uint16_t* x_perm, const int32_t* offsets,
+                        const uint16_t* w_gate, const uint16_t* w_up, const uint16_t* w_down,
+                        uint16_t* y_perm, uint16_t* save_g, uint16_t* save_u,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of moe_grouped_ffn_fwd.  Per expert e over its rows:
+ *   dH = dY W_down[e]^T;  dW_down[e] = H^T dY;  dG = dH * U * silu'(G);  dU = dH * silu(G);
+ *   dW_gate[e] = X^T dG;  dW_up[e] = X^T dU;  dX = dG W_gate[e]^T + dU W_up[e]^T.
+ *   dy_perm [N,d] bf16 in;  save_g, save_u as written by the forward call
+ *   dx_perm [N,d] bf16 out
+ *   dw_gate, dw_up [E',d,f] fp32, dw_down [E',f,d] fp32: overwritten when accumulate == 0 (experts without
+ *   rows get zeros), added to when accumulate == 1 (experts without rows are left untouched). */
+int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_perm, const uint16_t* x_perm,
+                        const int32_t* offsets, const uint16_t* w_gate, const uint16_t* w_up,
+                        const uint16_t* w_down, const uint16_t* save_g, const uint16_t* save_u,
+                        uint16_t* dx_perm, float* dw_gate, float* dw_up, float* dw_down, int accumulate,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* Local unpack + weighted combine (the per-GPU half of the combine of Section III-B):
+ *   out[t] = sum_{j<K'} topk_w[t,j] * y_perm[row_of_slot[t*K'+j]]   (fp32 accumulate in slot order, one bf16
+ *   rounding).   y_perm [N,d] bf16 in;  row_of_slot [N] int32 in;  topk_w [T,K'] fp32 in;  out [T,d] bf16. */
+int moe_unpermute_combine(const moe_shape* shape, const uint16_t* y_perm, const int32_t* row_of_slot,
+                          const float* topk_w, uint16_t* out, void* stream);
+
+/* Derivative of the combine:
+ *   dy_perm[row_of_slot[s]] = bf16( topk_w[s] * dout[t(s)] );   dtopk_w[t,j] = <dout[t], y_perm[row]> (fp32).
+ *   dout [T,d] bf16 in;  dy_perm [N,d] bf16 out;  dtopk_w [T,K'] fp32 out. */
+int moe_unpermute_combine_bwd(const moe_shape* shape, const uint16_t* dout, const uint16_t* y_perm,
+                              const int32_t* row_of_slot, const float* topk_w, uint16_t* dy_perm,
+                              float* dtopk_w, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

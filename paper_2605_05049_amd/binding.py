@@ -1,0 +1,234 @@
+"""ctypes binding of libmoe_gfx950.so.  Argument marshalling only; see include/moe.h for the semantics."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char_p, c_int, c_int32, c_size_t, c_void_p
+from typing import Optional
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libmoe_gfx950.so"
+_lib = None
+
+EXPORTED_SYMBOLS = (
+    "moe_status_str", "moe_workspace_bytes", "moe_abi_version",
+    "moe_route_topk", "moe_route_topk_bwd", "moe_permute", "moe_permute_bwd",
+    "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_unpermute_combine_bwd",
+)
+
+
+class MoeError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} failed: {status} ({status_str(status)})")
+
+
+class _CShape(Structure):
+    _fields_ = [("T", c_int32), ("d_model", c_int32), ("d_ffn", c_int32), ("E", c_int32), ("k", c_int32),
+                ("E_shared", c_int32), ("renorm", c_int32)]
+
+
+class Shape:
+    """Problem statement of one layer: T tokens, d_model, d_ffn, E routed experts, top-k, E_shared, renorm."""
+
+    def __init__(self, T, d_model, d_ffn, E, k, E_shared=0, renorm=1):
+        self.T, self.d_model, self.d_ffn, self.E, self.k = int(T), int(d_model), int(d_ffn), int(E), int(k)
+        self.E_shared, self.renorm = int(E_shared), int(renorm)
+        self._c = _CShape(self.T, self.d_model, self.d_ffn, self.E, self.k, self.E_shared, self.renorm)
+
+    @classmethod
+    def of(cls, s) -> "Shape":
+        """From any object with the same attribute names (e.g. a workloads.MoEShape)."""
+        return s if isinstance(s, Shape) else cls(s.T, s.d_model, s.d_ffn, s.E, s.k, s.E_shared, s.renorm)
+
+    E_total = property(lambda self: self.E + self.E_shared)
+    K_slots = property(lambda self: self.k + self.E_shared)
+    N = property(lambda self: self.T * (self.k + self.E_shared))
+
+
+def library_path() -> str:
+    return os.path.join(PKG_DIR, _LIB_NAME)
+
+
+def load_library():
+    """Loads the shared library (once).  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                           "(or python paper_2605_05049_amd/build.py) first; there is no CPU fallback")
+    lib = ctypes.CDLL(path)
+    sp = POINTER(_CShape)
+    lib.moe_status_str.restype = c_char_p
+    lib.moe_status_str.argtypes = [c_int]
+    lib.moe_workspace_bytes.restype = c_size_t
+    lib.moe_workspace_bytes.argtypes = [sp]
+    lib.moe_abi_version.restype = c_int
+    lib.moe_abi_version.argtypes = []
+    V = c_void_p
+    sigs = {
+        "moe_route_topk": [sp, V, V, V, V, V],
+        "moe_route_topk_bwd": [sp, V, V, V, V, V, V],
+        "moe_permute": [sp, V, V, V, V, V, V, V, V, c_size_t, V],
+        "moe_permute_bwd": [sp, V, V, V, V],
+        "moe_grouped_ffn_fwd": [sp, V, V, V, V, V, V, V, V, V, c_size_t, V],
+        "moe_grouped_ffn_bwd": [sp, V, V, V, V, V, V, V, V, V, V, V, V, c_int, V, c_size_t, V],
+        "moe_unpermute_combine": [sp, V, V, V, V, V],
+        "moe_unpermute_combine_bwd": [sp, V, V, V, V, V, V, V],
+    }
+    for name, args in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype = c_int
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def status_str(status: int) -> str:
+    return load_library().moe_status_str(int(status)).decode()
+
+
+def abi_version() -> int:
+    return int(load_library().moe_abi_version())
+
+
+def workspace_bytes(shape) -> int:
+    return int(load_library().moe_workspace_bytes(ctypes.byref(Shape.of(shape)._c)))
+
+
+# ------------------------------------------------------------------------------------------------------------
+# marshalling helpers
+# ------------------------------------------------------------------------------------------------------------
+
+def _ptr(t, dtype=None, numel: Optional[int] = None, name: str = "tensor"):
+    """Device pointer of a contiguous CUDA(HIP) tensor, after checking dtype and element count."""
+    if t is None:
+        return None
+    import torch
+    if not t.is_cuda:
+        raise ValueError(f"{name}: expected a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: expected a contiguous tensor")
+    if dtype is not None:
+        ok = t.dtype in dtype if isinstance(dtype, (tuple, list)) else t.dtype == dtype
+        if not ok:
+            raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name}: {t.numel()} elements, need {numel}")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return c_void_p(s.cuda_stream)
+
+
+def _check(fn: str, rc: int):
+    if rc != 0:
+        raise MoeError(fn, rc)
+
+
+def _bf16_types():
+    import torch
+    return (torch.bfloat16, torch.int16, torch.uint16)
+
+
+# ------------------------------------------------------------------------------------------------------------
+# entry points (same names and argument order as include/moe.h)
+# ------------------------------------------------------------------------------------------------------------
+
+def moe_route_topk(shape, logits, topk_idx, topk_w, probs_save=None, stream=None):
+    import torch
+    s = Shape.of(shape)
+    rc = load_library().moe_route_topk(
+        ctypes.byref(s._c), _ptr(logits, torch.float32, s.T * s.E, "logits"),
+        _ptr(topk_idx, torch.int32, s.N, "topk_idx"), _ptr(topk_w, torch.float32, s.N, "topk_w"),
+        _ptr(probs_save, torch.float32, s.T * s.E, "probs_save"), _stream(stream))
+    _check("moe_route_topk", rc)
+
+
+def moe_route_topk_bwd(shape, dtopk_w, topk_idx, topk_w, probs_save, dlogits, stream=None):
+    import torch
+    s = Shape.of(shape)
+    rc = load_library().moe_route_topk_bwd(
+        ctypes.byref(s._c), _ptr(dtopk_w, torch.float32, s.N, "dtopk_w"), _ptr(topk_idx, torch.int32, s.N, "topk_idx"),
+        _ptr(topk_w, torch.float32, s.N, "topk_w"), _ptr(probs_save, torch.float32, s.T * s.E, "probs_save"),
+        _ptr(dlogits, torch.float32, s.T * s.E, "dlogits"), _stream(stream))
+    _check("moe_route_topk_bwd", rc)
+
+
+def moe_permute(shape, x, topk_idx, x_perm, counts, offsets, row_of_slot, slot_of_row, ws, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    rc = load_library().moe_permute(
+        ctypes.byref(s._c), _ptr(x, bf, s.T * s.d_model, "x"), _ptr(topk_idx, torch.int32, s.N, "topk_idx"),
+        _ptr(x_perm, bf, s.N * s.d_model, "x_perm"), _ptr(counts, torch.int32, s.E_total, "counts"),
+        _ptr(offsets, torch.int32, s.E_total + 1, "offsets"), _ptr(row_of_slot, torch.int32, s.N, "row_of_slot"),
+        _ptr(slot_of_row, torch.int32, s.N, "slot_of_row"), _ptr(ws, None, None, "ws"),
+        ws.numel() * ws.element_size(), _stream(stream))
+    _check("moe_permute", rc)
+
+
+def moe_permute_bwd(shape, dx_perm, row_of_slot, dx, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    rc = load_library().moe_permute_bwd(
+        ctypes.byref(s._c), _ptr(dx_perm, bf, s.N * s.d_model, "dx_perm"),
+        _ptr(row_of_slot, torch.int32, s.N, "row_of_slot"), _ptr(dx, bf, s.T * s.d_model, "dx"), _stream(stream))
+    _check("moe_permute_bwd", rc)
+
+
+def moe_grouped_ffn_fwd(shape, x_perm, offsets, w_gate, w_up, w_down, y_perm, save_g, save_u, ws, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    nw = s.E_total * s.d_model * s.d_ffn
+    rc = load_library().moe_grouped_ffn_fwd(
+        ctypes.byref(s._c), _ptr(x_perm, bf, s.N * s.d_model, "x_perm"), _ptr(offsets, torch.int32, s.E_total + 1, "offsets"),
+        _ptr(w_gate, bf, nw, "w_gate"), _ptr(w_up, bf, nw, "w_up"), _ptr(w_down, bf, nw, "w_down"),
+        _ptr(y_perm, bf, s.N * s.d_model, "y_perm"), _ptr(save_g, bf, s.N * s.d_ffn, "save_g"),
+        _ptr(save_u, bf, s.N * s.d_ffn, "save_u"), _ptr(ws, None, None, "ws"), ws.numel() * ws.element_size(),
+        _stream(stream))
+    _check("moe_grouped_ffn_fwd", rc)
+
+
+def moe_grouped_ffn_bwd(shape, dy_perm, x_perm, offsets, w_gate, w_up, w_down, save_g, save_u, dx_perm,
+                        dw_gate, dw_up, dw_down, accumulate, ws, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    nw = s.E_total * s.d_model * s.d_ffn
+    rc = load_library().moe_grouped_ffn_bwd(
+        ctypes.byref(s._c), _ptr(dy_perm, bf, s.N * s.d_model, "dy_perm"), _ptr(x_perm, bf, s.N * s.d_model, "x_perm"),
+        _ptr(offsets, torch.int32, s.E_total + 1, "offsets"), _ptr(w_gate, bf, nw, "w_gate"), _ptr(w_up, bf, nw, "w_up"),
+        _ptr(w_down, bf, nw, "w_down"), _ptr(save_g, bf, s.N * s.d_ffn, "save_g"), _ptr(save_u, bf, s.N * s.d_ffn, "save_u"),
+        _ptr(dx_perm, bf, s.N * s.d_model, "dx_perm"), _ptr(dw_gate, torch.float32, nw, "dw_gate"),
+        _ptr(dw_up, torch.float32, nw, "dw_up"), _ptr(dw_down, torch.float32, nw, "dw_down"), int(bool(accumulate)),
+        _ptr(ws, None, None, "ws"), ws.numel() * ws.element_size(), _stream(stream))
+    _check("moe_grouped_ffn_bwd", rc)
+
+
+def moe_unpermute_combine(shape, y_perm, row_of_slot, topk_w, out, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    rc = load_library().moe_unpermute_combine(
+        ctypes.byref(s._c), _ptr(y_perm, bf, s.N * s.d_model, "y_perm"), _ptr(row_of_slot, torch.int32, s.N, "row_of_slot"),
+        _ptr(topk_w, torch.float32, s.N, "topk_w"), _ptr(out, bf, s.T * s.d_model, "out"), _stream(stream))
+    _check("moe_unpermute_combine", rc)
+
+
+def moe_unpermute_combine_bwd(shape, dout, y_perm, row_of_slot, topk_w, dy_perm, dtopk_w, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    rc = load_library().moe_unpermute_combine_bwd(
+        ctypes.byref(s._c), _ptr(dout, bf, s.T * s.d_model, "dout"), _ptr(y_perm, bf, s.N * s.d_model, "y_perm"),
+        _ptr(row_of_slot, torch.int32, s.N, "row_of_slot"), _ptr(topk_w, torch.float32, s.N, "topk_w"),
+        _ptr(dy_perm, bf, s.N * s.d_model, "dy_perm"), _ptr(dtopk_w, torch.float32, s.N, "dtopk_w"), _stream(stream))
+    _check("moe_unpermute_combine_bwd", rc)

@@ -1,0 +1,99 @@
+// Shared host/device helpers of the gfx950 MoE library: argument checks, workspace layout, bf16 conversion.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/moe.h"
+
+namespace moe {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kMaxExperts = 1024;    // E' limit of the ABI
+constexpr int kPermSlotsPerBlock = 1024;  // slots ranked by one block of the counting sort
+constexpr int kMinTileRows = 32;     // smallest row-tile height any GEMM schedule may use
+
+struct Dims {
+  int T, d, f, E, k, Es, Et, Kp, renorm;
+  long long N;
+};
+
+// Validates a shape against the ABI limits and fills the derived sizes.
+inline int check_shape(const moe_shape* s, Dims* out) {
+  if (!s) return MOE_ERR_NULL;
+  if (s->T < 0 || s->E < 1 || s->k < 1 || s->k > s->E || s->E_shared < 0) return MOE_ERR_SHAPE;
+  if (s->E > kMaxExperts || (long long)s->E + s->E_shared > kMaxExperts) return MOE_ERR_SHAPE;
+  if (s->d_model <= 0 || s->d_ffn <= 0 || (s->d_model % 64) || (s->d_ffn % 64)) return MOE_ERR_SHAPE;
+  long long Kp = (long long)s->k + s->E_shared;
+  long long N = (long long)s->T * Kp;
+  if (N >= (1ll << 31)) return MOE_ERR_SHAPE;
+  out->T = s->T; out->d = s->d_model; out->f = s->d_ffn; out->E = s->E; out->k = s->k; out->Es = s->E_shared;
+  out->Et = s->E + s->E_shared; out->Kp = (int)Kp; out->N = N; out->renorm = s->renorm ? 1 : 0;
+  return MOE_OK;
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Workspace carve-up.  Every region starts 256-byte aligned.
+//   perm_hist : per-block expert histograms of the counting sort, then turned into per-block bases
+//   perm_rank : rank of every slot among the same-expert slots of its block
+//   sched     : tile schedule of the grouped GEMMs (header + two int arrays)
+//   h, dg, du : bf16 [N,f] intermediates of the expert FFN (H in forward; H, dG, dU in backward)
+struct WsLayout {
+  size_t perm_hist, perm_hist_bytes;
+  size_t perm_rank, perm_rank_bytes;
+  size_t sched, sched_bytes;
+  size_t h, dg, du, nf_bytes;
+  size_t total;
+};
+
+inline int perm_num_blocks(long long N) { return (int)((N + kPermSlotsPerBlock - 1) / kPermSlotsPerBlock); }
+inline long long sched_max_tiles(const Dims& D) { return D.N / kMinTileRows + D.Et; }
+
+inline WsLayout ws_layout(const Dims& D) {
+  WsLayout L;
+  size_t off = 0;
+  L.perm_hist = off;
+  L.perm_hist_bytes = round_up((size_t)perm_num_blocks(D.N) * D.Et * sizeof(int32_t) + 256, 256);
+  off += L.perm_hist_bytes;
+  L.perm_rank = off;
+  L.perm_rank_bytes = round_up((size_t)D.N * sizeof(int32_t) + 256, 256);
+  off += L.perm_rank_bytes;
+  L.sched = off;
+  L.sched_bytes = round_up((size_t)(64 + 2 * sched_max_tiles(D)) * sizeof(int32_t), 256);
+  off += L.sched_bytes;
+  L.nf_bytes = round_up((size_t)D.N * D.f * sizeof(uint16_t), 256);
+  L.h = off; off += L.nf_bytes;
+  L.dg = off; off += L.nf_bytes;
+  L.du = off; off += L.nf_bytes;
+  L.total = off;
+  return L;
+}
+
+#define MOE_REQUIRE_PTR(p) do { if ((p) == nullptr) return MOE_ERR_NULL; } while (0)
+#define MOE_REQUIRE_ALIGNED(p) do { if (!::moe::aligned((p), 16)) return MOE_ERR_ALIGN; } while (0)
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_RUNTIME; }
+
+// ---------------------------------------------------------------------------------------------------------
+// device helpers
+// ---------------------------------------------------------------------------------------------------------
+
+// bf16 <-> fp32 on raw bit patterns.  Round-to-nearest-even; NaN stays NaN.
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float v) {
+  uint32_t u = __float_as_uint(v);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+}  // namespace moe

@@ -1,0 +1,65 @@
+"""Buffer set and call order of one MoE expert layer step.  Torch is used for device memory only: every
+computation is one of the C-ABI entry points, called in the order of the per-layer flow (routing -> pack ->
+experts -> unpack/combine, then the reverse for backward)."""
+from __future__ import annotations
+
+from . import binding as B
+
+
+class MoeLayerBuffers:
+    """All device buffers one forward+backward of a layer touches, allocated once."""
+
+    def __init__(self, shape, device="cuda", with_backward=True, with_router=True):
+        import torch
+        s = B.Shape.of(shape)
+        self.shape = s
+        dev = torch.device(device)
+        bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+        N, T, d, f, Et, Kp = s.N, s.T, s.d_model, s.d_ffn, s.E_total, s.K_slots
+        e = lambda *sz, dtype: torch.empty(*sz, dtype=dtype, device=dev)  # noqa: E731
+        self.topk_idx = e(T, Kp, dtype=i32)
+        self.topk_w = e(T, Kp, dtype=f32)
+        self.probs = e(T, s.E, dtype=f32) if with_router else None
+        self.counts = e(Et, dtype=i32)
+        self.offsets = e(Et + 1, dtype=i32)
+        self.row_of_slot = e(N, dtype=i32)
+        self.slot_of_row = e(N, dtype=i32)
+        self.x_perm = e(N, d, dtype=bf)
+        self.save_g = e(N, f, dtype=bf)
+        self.save_u = e(N, f, dtype=bf)
+        self.y_perm = e(N, d, dtype=bf)
+        self.out = e(T, d, dtype=bf)
+        self.ws = torch.empty(max(B.workspace_bytes(s), 256), dtype=torch.uint8, device=dev)
+        if with_backward:
+            self.dy_perm = e(N, d, dtype=bf)
+            self.dtopk_w = e(T, Kp, dtype=f32)
+            self.dx_perm = e(N, d, dtype=bf)
+            self.dx = e(T, d, dtype=bf)
+            self.dw_gate = e(Et, d, f, dtype=f32)
+            self.dw_up = e(Et, d, f, dtype=f32)
+            self.dw_down = e(Et, f, d, dtype=f32)
+            self.dlogits = e(T, s.E, dtype=f32) if with_router else None
+
+
+def layer_forward(buf: MoeLayerBuffers, x, w_gate, w_up, w_down, logits=None, stream=None):
+    """routing (skipped when logits is None: buf.topk_idx / buf.topk_w were filled by the caller, as for an
+    expert-parallel shard) -> permute -> grouped FFN -> combine.  Returns buf.out."""
+    s = buf.shape
+    if logits is not None:
+        B.moe_route_topk(s, logits, buf.topk_idx, buf.topk_w, buf.probs, stream)
+    B.moe_permute(s, x, buf.topk_idx, buf.x_perm, buf.counts, buf.offsets, buf.row_of_slot, buf.slot_of_row, buf.ws, stream)
+    B.moe_grouped_ffn_fwd(s, buf.x_perm, buf.offsets, w_gate, w_up, w_down, buf.y_perm, buf.save_g, buf.save_u, buf.ws, stream)
+    B.moe_unpermute_combine(s, buf.y_perm, buf.row_of_slot, buf.topk_w, buf.out, stream)
+    return buf.out
+
+
+def layer_backward(buf: MoeLayerBuffers, dout, w_gate, w_up, w_down, accumulate=False, with_router=True, stream=None):
+    """combine_bwd -> grouped FFN bwd -> permute_bwd -> route_bwd.  Results land in buf.dx, buf.dw_*, buf.dtopk_w,
+    buf.dlogits."""
+    s = buf.shape
+    B.moe_unpermute_combine_bwd(s, dout, buf.y_perm, buf.row_of_slot, buf.topk_w, buf.dy_perm, buf.dtopk_w, stream)
+    B.moe_grouped_ffn_bwd(s, buf.dy_perm, buf.x_perm, buf.offsets, w_gate, w_up, w_down, buf.save_g, buf.save_u,
+                          buf.dx_perm, buf.dw_gate, buf.dw_up, buf.dw_down, accumulate, buf.ws, stream)
+    B.moe_permute_bwd(s, buf.dx_perm, buf.row_of_slot, buf.dx, stream)
+    if with_router and buf.dlogits is not None:
+        B.moe_route_topk_bwd(s, buf.dtopk_w, buf.topk_idx, buf.topk_w, buf.probs, buf.dlogits, stream)

@@ -222,6 +222,7 @@ def test_silu_closed_forms():
     z = np.linspace(-6, 6, 25)
     h = 1e-6
     np.testing.assert_allclose(O.silu_grad(z), (O.silu(z + h) - O.silu(z - h)) / (2 * h), rtol=1e-8, atol=1e-9)
+    np.testing.assert_allclose(O.silu_grad2(z), (O.silu_grad(z + h) - O.silu_grad(z - h)) / (2 * h), rtol=1e-7, atol=1e-9)
 
 
 @pytest.mark.parametrize("E_shared", [0, 1])
@@ -396,13 +397,35 @@ def test_grouped_ffn_slices():
     np.testing.assert_allclose(dWds, dWd[:, [4, 1], :], rtol=1e-13)
 
 
-def test_error_measures():
-    ref = np.array([1.0, -2.0, 0.0, 4.0])
-    got = ref + np.array([0.0, 0.04, 0.0, -0.02])
+def test_error_measures_and_scales():
+    ref = np.array([[1.0, -2.0], [0.0, 4.0]])
+    got = ref + np.array([[0.0, 0.04], [0.0, -0.02]])
     assert abs(O.rel_to_max_error(got, ref) - 0.01) < 1e-15
-    rms = math.sqrt((1 + 4 + 16) / 4)
-    assert abs(O.elementwise_excess(got, ref, 0.01) - (0.04 - 0.02 - 0.01 * rms)) < 1e-15
     assert O.rel_to_max_error(np.zeros(3), np.zeros(3)) == 0.0
+    scale = np.array([[0.5, 1.0], [2.0, 0.0]])
+    exc = max(0.04 - 0.01 * (2.0 + 1.0), 0.02 - 0.01 * 4.0, -0.01 * 1.5, -0.01 * 2.0)
+    assert abs(O.elementwise_excess(got, ref, scale, 0.01) - exc) < 1e-15
+    # quadrature magnitude by loops; a one-term contraction has scale |value|
+    rng = np.random.default_rng(0)
+    a, b = rng.standard_normal((3, 5)), rng.standard_normal((5, 4))
+    q = O.quad(a, b)
+    for i in range(3):
+        for j in range(4):
+            assert abs(q[i, j] - math.sqrt(sum((a[i, n] * b[n, j]) ** 2 for n in range(5)))) < 1e-14
+    np.testing.assert_allclose(O.quad(a[:, :1], b[:1]), np.abs(a[:, :1] @ b[:1]), rtol=1e-14)
+    # stage scales: shapes follow the outputs, empty experts have scale 0, and scale >= |value| / sqrt(terms)
+    x, Wg, Wu, Wd, logits, dout = small_case(T=9, d=4, f=6, E=5, k=2, seed=4)
+    logits[:, 3] = -1e30
+    idx, w, _ = O.route_topk(logits, 2, 0, True)
+    sc = O.layer_scales(x, idx, w, Wg, Wu, Wd, dout, 5)
+    g = O.layer_backward(x, idx, w, Wg, Wu, Wd, dout)
+    out, _ = O.layer_forward(x, idx, w, Wg, Wu, Wd)
+    assert sc["out"].shape == out.shape and sc["dx"].shape == g["dx"].shape
+    assert sc["dtopk_w"].shape == g["dtopk_w"].shape
+    for key in ("dw_gate", "dw_up", "dw_down"):
+        assert sc[key].shape == g[key].shape and not np.any(sc[key][3]) and np.all(sc[key] >= 0)
+        n_terms = 18
+        assert np.all(sc[key] * math.sqrt(n_terms) >= np.abs(g[key]) - 1e-12)     # Cauchy-Schwarz
 
 
 # ---------------------------------------------------------------------------------------------------------

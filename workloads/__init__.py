@@ -102,11 +102,13 @@ WORKLOADS: Dict[str, Workload] = {
 
 
 def scaled_down(w: Workload, dim_div: int = 8, tok_div: int = 4) -> Workload:
-    """Same E, k and routing recipe with d, f divided by dim_div and T by tok_div (full-oracle sized copy)."""
+    """Same E, k and routing recipe with d, f divided by dim_div (rounded up to a multiple of 64) and T by
+    tok_div: a copy small enough for the full fp64 oracle."""
     s = w.shape
+    r64 = lambda v: max(64, -(-v // 64) * 64)  # noqa: E731
     return replace(w, name=w.name + "_small",
-                   shape=replace(s, T=max(s.T // tok_div, 1), d_model=s.d_model // dim_div,
-                                 d_ffn=s.d_ffn // dim_div))
+                   shape=replace(s, T=max(s.T // tok_div, 1), d_model=r64(s.d_model // dim_div),
+                                 d_ffn=r64(s.d_ffn // dim_div)))
 
 
 # --------------------------------------------------------------------------------------------------------------
