@@ -1,0 +1,282 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE expert layer on one MI355X: one step = one forward + backward pass of the whole hot path
+(route -> permute -> grouped FFN -> combine, then combine_bwd -> grouped FFN bwd -> permute_bwd -> route_bwd) over one
+batch of seeded synthetic input already resident in HBM.
+
+Prints ONE JSON line.  `value` is fwd+bwd TFLOP/s with FLOPs = 18*d*f*N (three 2*d*f GEMMs per permuted row forward,
+twice that backward; padded rows and empty experts are never counted).  `roofline` prices the slowest kernel of the
+step against the bf16 dense MFMA peak from per-launch HIP-event timings taken live in a second, instrumented pass.
+`permute_combine` reports the streaming kernels' HBM rate on the imbalance workload.  `cpu_baseline` times the fp64
+oracle on a bounded sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="mixtral", help="mixtral (headline) | tiny | finegrained | shard | imbalance")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-streaming", action="store_true", help="skip the permute/combine bandwidth measurement")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens of the workload the oracle is timed on (0 = auto)")
+    return ap.parse_args()
+
+
+def dev_bf16(bits):
+    import numpy as np
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def gemm_flops_per_launch(label, shape):
+    """Algorithmic FLOPs of one launch of each grouped-GEMM kernel: 2*d*f per row and matrix."""
+    unit = 2.0 * shape.d_model * shape.d_ffn * shape.N
+    return {"ffn_fwd_gate_up_swiglu": 2 * unit, "ffn_fwd_down": unit, "ffn_bwd_dh_dswiglu": unit,
+            "ffn_bwd_dx": 2 * unit, "ffn_bwd_dw_down": unit, "ffn_bwd_dw_gate_up": 2 * unit}.get(label)
+
+
+def stream_bytes_per_launch(label, shape):
+    """Algorithmic HBM bytes of one launch of each streaming kernel (bf16 rows + int32 maps + fp32 weights)."""
+    T, d, N = shape.T, shape.d_model, shape.N
+    return {
+        "perm_scatter_gather": T * d * 2 + N * d * 2 + N * 4 * 4,       # read x once, write x_perm, idx+rank in, 2 maps out
+        "unpermute_combine": N * d * 2 + N * 8 + T * d * 2,
+        "unpermute_combine_bwd": T * d * 2 + 2 * N * d * 2 + N * 12,
+        "permute_bwd": N * d * 2 + N * 4 + T * d * 2,
+    }.get(label)
+
+
+def run_layer_bench(moe, W, args):
+    import torch
+    wl = W.WORKLOADS[args.workload]
+    sh = wl.shape
+    t0 = time.time()
+    inp = W.make_layer_inputs(wl, seed=args.seed)
+    gen_s = time.time() - t0
+    s = moe.Shape.of(sh)
+    buf = moe.MoeLayerBuffers(s)
+    x, dout = dev_bf16(inp["x"]), dev_bf16(inp["dout"])
+    wg, wu, wd = dev_bf16(inp["w_gate"]), dev_bf16(inp["w_up"]), dev_bf16(inp["w_down"])
+    if "logits" in inp:
+        logits = torch.from_numpy(inp["logits"]).cuda()
+    else:
+        logits = None
+        buf.topk_idx.copy_(torch.from_numpy(inp["topk_idx"]).cuda())
+        buf.topk_w.copy_(torch.from_numpy(inp["topk_w"]).cuda())
+
+    def step():
+        moe.layer_forward(buf, x, wg, wu, wd, logits)
+        moe.layer_backward(buf, dout, wg, wu, wd, accumulate=False, with_router=logits is not None)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # instrumented pass: per-launch HIP events on the launch stream
+    moe.profile_reset()
+    moe.profile_enable(True)
+    prof_steps = max(1, min(args.steps, 5))
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    moe.profile_enable(False)
+    recs = moe.profile_records()
+    moe.profile_reset()
+    per_kernel = {}
+    for name, ms in recs:
+        per_kernel.setdefault(name, []).append(ms)
+    kernels = {k: {"launches_per_step": len(v) // prof_steps, "avg_ms": sum(v) / len(v)} for k, v in per_kernel.items()}
+    return inp, sh, elapsed, kernels, gen_s
+
+
+def run_streaming_bench(moe, W, steps):
+    """permute / combine family on the imbalance workload's shape (working set 671 MB per kernel, larger than the
+    256 MB last-level cache); two buffer sets are alternated so no launch re-reads what the previous one wrote."""
+    import numpy as np
+    import torch
+    wl = W.WORKLOADS["imbalance"]
+    sh = wl.shape
+    s = moe.Shape.of(sh)
+    logits, _ = W.make_forced_imbalance_logits(sh, seed=0)
+    d_logits = torch.from_numpy(logits).cuda()
+    N, T, d, Kp, Et = s.N, s.T, s.d_model, s.K_slots, s.E_total
+    sets = []
+    for i in range(2):
+        x = dev_bf16(W.make_tokens(sh, seed=i))
+        sets.append(dict(
+            x=x, dout=dev_bf16(W.make_dout(sh, seed=i)),
+            x_perm=torch.empty((N, d), dtype=torch.bfloat16, device="cuda"),
+            y_perm=torch.randn((N, d), device="cuda").to(torch.bfloat16),
+            dy_perm=torch.empty((N, d), dtype=torch.bfloat16, device="cuda"),
+            out=torch.empty((T, d), dtype=torch.bfloat16, device="cuda"),
+            dx=torch.empty((T, d), dtype=torch.bfloat16, device="cuda"),
+            dtw=torch.empty((T, Kp), dtype=torch.float32, device="cuda")))
+    idx = torch.empty((T, Kp), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, Kp), dtype=torch.float32, device="cuda")
+    counts = torch.empty((Et,), dtype=torch.int32, device="cuda")
+    offsets = torch.empty((Et + 1,), dtype=torch.int32, device="cuda")
+    ros = torch.empty((N,), dtype=torch.int32, device="cuda")
+    sor = torch.empty((N,), dtype=torch.int32, device="cuda")
+    ws = torch.empty(moe.workspace_bytes(s), dtype=torch.uint8, device="cuda")
+    moe.moe_route_topk(s, d_logits, idx, w, None)
+
+    def one(i):
+        b = sets[i % 2]
+        moe.moe_permute(s, b["x"], idx, b["x_perm"], counts, offsets, ros, sor, ws)
+        moe.moe_unpermute_combine(s, b["y_perm"], ros, w, b["out"])
+        moe.moe_unpermute_combine_bwd(s, b["dout"], b["y_perm"], ros, w, b["dy_perm"], b["dtw"])
+        moe.moe_permute_bwd(s, b["y_perm"], ros, b["dx"])
+
+    for i in range(4):
+        one(i)
+    torch.cuda.synchronize()
+    moe.profile_reset()
+    moe.profile_enable(True)
+    for i in range(steps):
+        one(i)
+    torch.cuda.synchronize()
+    moe.profile_enable(False)
+    recs = moe.profile_records()
+    moe.profile_reset()
+    per = {}
+    for name, ms in recs:
+        per.setdefault(name, []).append(ms)
+    out = {"workload": "imbalance: T=16384 d=4096 E=128 top-4 (N=65536)", "peak_GBs": PEAK_HBM_GBS, "kernels": {}}
+    for name, v in per.items():
+        avg = sum(v) / len(v)
+        b = stream_bytes_per_launch(name, sh)
+        ent = {"avg_us": round(avg * 1e3, 2)}
+        if b:
+            ent["algorithmic_MB"] = round(b / 1e6, 1)
+            ent["GBs"] = round(b / (avg * 1e-3) / 1e9, 1)
+            ent["frac_hbm_peak"] = round(b / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+        out["kernels"][name] = ent
+    pk = [k for k in ("perm_rank", "perm_scan", "perm_scatter_gather") if k in per]
+    tot = sum(sum(per[k]) / len(per[k]) for k in pk)
+    b = stream_bytes_per_launch("perm_scatter_gather", sh)
+    out["moe_permute_total"] = {"avg_us": round(tot * 1e3, 2), "GBs": round(b / (tot * 1e-3) / 1e9, 1),
+                                "frac_hbm_peak": round(b / (tot * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    del sets
+    torch.cuda.empty_cache()
+    return out
+
+
+def run_cpu_baseline(W, inp, sh, sample_tokens):
+    """The fp64 oracle, as it stands, on the first `sample_tokens` tokens of the same workload (all experts, same
+    routing): forward + backward of the per-token definition.  Rate = algorithmic FLOPs of the sample / wall time."""
+    import numpy as np
+    from oracle import moe_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    f = W.bf16_bits_to_f32
+    n = min(sample_tokens, sh.T)
+    x, dout = f(inp["x"][:n]), f(inp["dout"][:n])
+    if "logits" in inp:
+        idx, w, _ = O.route_topk(inp["logits"][:n], sh.k, sh.E_shared, True)
+    else:
+        idx, w = inp["topk_idx"][:n], inp["topk_w"][:n].astype(np.float64)
+    t0 = time.perf_counter()
+    wg, wu, wd = f(inp["w_gate"]), f(inp["w_up"]), f(inp["w_down"])
+    out, _ = O.layer_forward(x, idx, w, wg, wu, wd)
+    g = O.layer_backward(x, idx, w, wg, wu, wd, dout)
+    dt = time.perf_counter() - t0
+    flops = 18.0 * sh.d_model * sh.d_ffn * n * sh.K_slots
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"fp64 NumPy oracle fwd+bwd on the first {n} of {sh.T} tokens of the same workload "
+                      f"(all {sh.E_total} experts, {n * sh.K_slots} slots, {flops / 1e12:.3f} TFLOP) in {dt:.1f} s",
+            "seconds": round(dt, 2)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU's MoE expert layer; this build has no multi-GPU path "
+              "(run with --gpus 1).", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2605_05049_amd as moe
+    import workloads as W
+    moe.load_library()      # raises if the HIP library is missing: no fallback
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    inp, sh, elapsed, kernels, gen_s = run_layer_bench(moe, W, args)
+    flops = sh.flops_fwd_bwd()
+    ms_per_step = elapsed / args.steps * 1e3
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+
+    # roofline of the dominant kernel (largest total time per step)
+    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches_per_step"])
+    dom_flops = gemm_flops_per_launch(dom, sh)
+    if dom_flops:
+        ach = dom_flops / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None, "kernel": dom,
+                    "avg_ms": round(kernels[dom]["avg_ms"], 4), "flops_per_launch": dom_flops}
+    else:
+        b = stream_bytes_per_launch(dom, sh) or 0
+        ach = b / (kernels[dom]["avg_ms"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None, "kernel": dom,
+                    "avg_ms": round(kernels[dom]["avg_ms"], 4)}
+    kern_out = {}
+    for k, v in sorted(kernels.items(), key=lambda kv: -kv[1]["avg_ms"] * kv[1]["launches_per_step"]):
+        ent = {"avg_ms": round(v["avg_ms"], 4), "launches_per_step": v["launches_per_step"]}
+        fl = gemm_flops_per_launch(k, sh)
+        if fl:
+            ent["TFLOPs"] = round(fl / (v["avg_ms"] * 1e-3) / 1e12, 1)
+            ent["frac_mfma_peak"] = round(ent["TFLOPs"] / PEAK_BF16_MFMA_TFLOPS, 4)
+        kern_out[k] = ent
+
+    res = {
+        "metric": "MoE layer fwd+bwd TFLOP/s", "value": round(tflops, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: T={sh.T} d_model={sh.d_model} d_ffn={sh.d_ffn} E={sh.E}"
+                               f"+{sh.E_shared} shared top-{sh.k} (N={sh.N} rows), fwd+bwd, seed {args.seed}",
+                   "flops_per_step": flops},
+        "frac_bf16_mfma_peak": round(tflops / PEAK_BF16_MFMA_TFLOPS, 4),
+        "roofline": roofline,
+        "kernels": kern_out,
+    }
+    if not args.no_streaming:
+        res["permute_combine"] = run_streaming_bench(moe, W, steps=20)
+    if not args.no_cpu_baseline:
+        n = args.cpu_sample_tokens
+        if n <= 0:
+            # about 10-30 s of fp64 work: ~1 TFLOP at the ~50-100 GFLOP/s the host cores give NumPy
+            per_token = 18.0 * sh.d_model * sh.d_ffn * sh.K_slots
+            n = int(max(16, min(sh.T, 1.0e12 / per_token)))
+        res["cpu_baseline"] = run_cpu_baseline(W, inp, sh, n)
+    res["input_generation_s"] = round(gen_s, 1)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -64,6 +64,16 @@ size_t moe_workspace_bytes(const moe_shape* shape);
 /* Library version, for the binding's sanity check. */
 int moe_abi_version(void);
 
+/* Per-launch timing for benchmarks (host side; off by default).  While enabled, every kernel the library
+ * launches is bracketed by two HIP events recorded on the launch stream (this creates events, so it is not for
+ * callers that must not allocate).  moe_profile_get synchronises on record i and returns the kernel's label
+ * (a static string) and its elapsed milliseconds; moe_profile_reset drops all records.  Not thread-safe with
+ * respect to concurrent compute calls on other threads beyond a mutex around the record list. */
+int moe_profile_enable(int on);
+int moe_profile_count(void);
+int moe_profile_get(int i, const char** name, float* ms);
+int moe_profile_reset(void);
+
 /* Top-k softmax gating (Section II-A "learned gating function"; Section III-A symbols E, E_s, k).
  * Per token: p = softmax(logits[t, 0:E]) in fp32; the k largest LOGITS are selected (descending; equal
  * logits -> lower expert id first); topk_w[t,j] = p[idx], divided by the sum over the k selected when renorm.

@@ -12,6 +12,7 @@ _lib = None
 
 EXPORTED_SYMBOLS = (
     "moe_status_str", "moe_workspace_bytes", "moe_abi_version",
+    "moe_profile_enable", "moe_profile_count", "moe_profile_get", "moe_profile_reset",
     "moe_route_topk", "moe_route_topk_bwd", "moe_permute", "moe_permute_bwd",
     "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_unpermute_combine_bwd",
 )
@@ -67,6 +68,14 @@ def load_library():
     lib.moe_workspace_bytes.argtypes = [sp]
     lib.moe_abi_version.restype = c_int
     lib.moe_abi_version.argtypes = []
+    lib.moe_profile_enable.restype = c_int
+    lib.moe_profile_enable.argtypes = [c_int]
+    lib.moe_profile_count.restype = c_int
+    lib.moe_profile_count.argtypes = []
+    lib.moe_profile_get.restype = c_int
+    lib.moe_profile_get.argtypes = [c_int, POINTER(c_char_p), POINTER(ctypes.c_float)]
+    lib.moe_profile_reset.restype = c_int
+    lib.moe_profile_reset.argtypes = []
     V = c_void_p
     sigs = {
         "moe_route_topk": [sp, V, V, V, V, V],
@@ -96,6 +105,26 @@ def abi_version() -> int:
 
 def workspace_bytes(shape) -> int:
     return int(load_library().moe_workspace_bytes(ctypes.byref(Shape.of(shape)._c)))
+
+
+def profile_enable(on: bool) -> None:
+    _check("moe_profile_enable", load_library().moe_profile_enable(int(bool(on))))
+
+
+def profile_reset() -> None:
+    _check("moe_profile_reset", load_library().moe_profile_reset())
+
+
+def profile_records():
+    """[(label, milliseconds)] of every launch recorded since the last reset (synchronises on each)."""
+    lib = load_library()
+    out = []
+    for i in range(lib.moe_profile_count()):
+        name = c_char_p()
+        ms = ctypes.c_float()
+        _check("moe_profile_get", lib.moe_profile_get(i, ctypes.byref(name), ctypes.byref(ms)))
+        out.append((name.value.decode(), float(ms.value)))
+    return out
 
 
 # ------------------------------------------------------------------------------------------------------------

@@ -78,6 +78,22 @@ inline WsLayout ws_layout(const Dims& D) {
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_RUNTIME; }
 
+// Optional per-launch timing (moe_profile_* in the ABI).  While enabled, every kernel launch of the library is
+// bracketed by two HIP events on the launch stream; disabled (the default) it costs one branch.
+void prof_begin(const char* name, hipStream_t st);
+void prof_end(hipStream_t st);
+struct ProfScope {
+  hipStream_t st;
+  ProfScope(const char* name, hipStream_t s) : st(s) { prof_begin(name, s); }
+  ~ProfScope() { prof_end(st); }
+};
+// hipLaunchKernelGGL with a label for the optional per-launch timing.
+#define MOE_LAUNCH(label, st, ...)            \
+  do {                                        \
+    ::moe::ProfScope moe_prof_scope_(label, st); \
+    hipLaunchKernelGGL(__VA_ARGS__);          \
+  } while (0)
+
 // ---------------------------------------------------------------------------------------------------------
 // device helpers
 // ---------------------------------------------------------------------------------------------------------

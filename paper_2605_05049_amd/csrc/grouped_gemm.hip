@@ -360,11 +360,11 @@ __global__ __launch_bounds__(1024) void build_schedule_kernel(const int32_t* __r
 }
 
 template <int KIND, bool P_RC, bool Q_RC, int NQ, int NPASS, int EPI>
-static void launch_gemm(const GemmArgs& A, long long max_blocks, hipStream_t st) {
+static void launch_gemm(const char* label, const GemmArgs& A, long long max_blocks, hipStream_t st) {
   constexpr size_t lds = ((P_RC ? RC_TILE : KC_TILE) + NQ * (Q_RC ? RC_TILE : KC_TILE)) * sizeof(uint16_t);
   const long long grid = (max_blocks + kNumXcd - 1) / kNumXcd * kNumXcd;
   if (grid <= 0) return;
-  hipLaunchKernelGGL((grouped_gemm_kernel<KIND, P_RC, Q_RC, NQ, NPASS, EPI>), dim3((unsigned)grid), dim3(256), lds, st, A);
+  MOE_LAUNCH(label, st, (grouped_gemm_kernel<KIND, P_RC, Q_RC, NQ, NPASS, EPI>), dim3((unsigned)grid), dim3(256), lds, st, A);
 }
 
 static int common_checks(const moe_shape* shape, Dims* D, void* ws, size_t ws_bytes, WsLayout* L) {
@@ -399,7 +399,7 @@ extern "C" int moe_grouped_ffn_fwd(const moe_shape* shape, const uint16_t* x_per
   uint16_t* h = reinterpret_cast<uint16_t*>(wsb + L.h);
   const int max_tiles = (int)sched_max_tiles(D);
   const long long ub_tiles = D.N / TP + D.Et;  // sum_e ceil(n_e/128) <= N/128 + E'
-  hipLaunchKernelGGL(build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, D.Et, max_tiles);
+  MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, D.Et, max_tiles);
 
   GemmArgs A = {};
   A.sched = sched; A.max_tiles = max_tiles; A.offsets = offsets; A.Et = D.Et;
@@ -408,13 +408,13 @@ extern "C" int moe_grouped_ffn_fwd(const moe_shape* shape, const uint16_t* x_per
   A.p0 = x_perm; A.p_ld = D.d;
   A.q0 = w_gate; A.q1 = w_up; A.q_ld = D.f; A.q_expert_stride = (size_t)D.d * D.f;
   A.c0 = save_g; A.c1 = save_u; A.c2 = h; A.c_ld = D.f;
-  launch_gemm<0, false, true, 2, 1, EPI_SWIGLU>(A, ub_tiles * A.n_q_tiles, st);
+  launch_gemm<0, false, true, 2, 1, EPI_SWIGLU>("ffn_fwd_gate_up_swiglu", A, ub_tiles * A.n_q_tiles, st);
   // Y = H Wd
   A.n_q_tiles = (D.d + TQ - 1) / TQ; A.q_dim = D.d; A.k_dim = D.f;
   A.p0 = h; A.p_ld = D.f;
   A.q0 = w_down; A.q1 = nullptr; A.q_ld = D.d; A.q_expert_stride = (size_t)D.f * D.d;
   A.c0 = y_perm; A.c1 = nullptr; A.c2 = nullptr; A.c_ld = D.d;
-  launch_gemm<0, false, true, 1, 1, EPI_BF16>(A, ub_tiles * A.n_q_tiles, st);
+  launch_gemm<0, false, true, 1, 1, EPI_BF16>("ffn_fwd_down", A, ub_tiles * A.n_q_tiles, st);
   return launch_status();
 }
 
@@ -446,31 +446,31 @@ extern "C" int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_pe
   GemmArgs A = {};
   A.sched = sched; A.max_tiles = max_tiles; A.offsets = offsets; A.Et = D.Et; A.accumulate = accumulate ? 1 : 0;
   if (D.N > 0) {
-    hipLaunchKernelGGL(build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, D.Et, max_tiles);
+    MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, D.Et, max_tiles);
     // dH = dY Wd^T, then dG, dU and H from the saved G, U
     A.n_q_tiles = (D.f + TQ - 1) / TQ; A.q_dim = D.f; A.k_dim = D.d;
     A.p0 = dy_perm; A.p_ld = D.d;
     A.q0 = w_down; A.q_ld = D.d; A.q_expert_stride = (size_t)D.f * D.d;
     A.c0 = dg; A.c1 = du; A.c2 = h; A.c_ld = D.f; A.g_in = save_g; A.u_in = save_u;
-    launch_gemm<0, false, false, 1, 1, EPI_DSWIGLU>(A, ub_tiles * A.n_q_tiles, st);
+    launch_gemm<0, false, false, 1, 1, EPI_DSWIGLU>("ffn_bwd_dh_dswiglu", A, ub_tiles * A.n_q_tiles, st);
     // dX = dG Wg^T + dU Wu^T
     A.n_q_tiles = (D.d + TQ - 1) / TQ; A.q_dim = D.d; A.k_dim = D.f;
     A.p0 = dg; A.p1 = du; A.p_ld = D.f;
     A.q0 = w_gate; A.q1 = w_up; A.q_ld = D.f; A.q_expert_stride = (size_t)D.d * D.f;
     A.c0 = dx_perm; A.c1 = nullptr; A.c2 = nullptr; A.c_ld = D.d;
-    launch_gemm<0, false, false, 1, 2, EPI_BF16>(A, ub_tiles * A.n_q_tiles, st);
+    launch_gemm<0, false, false, 1, 2, EPI_BF16>("ffn_bwd_dx", A, ub_tiles * A.n_q_tiles, st);
   }
   // dWd[e] = H_e^T dY_e   (rows f, columns d)
   A.p_dim = D.f; A.n_p_tiles = (D.f + TP - 1) / TP; A.q_dim = D.d; A.n_q_tiles = (D.d + TQ - 1) / TQ;
   A.p0 = h; A.p1 = nullptr; A.p_ld = D.f;
   A.q0 = dy_perm; A.q1 = nullptr; A.q_ld = D.d;
   A.f0 = dw_down; A.f1 = nullptr; A.f_expert_stride = (size_t)D.f * D.d; A.c_ld = D.d;
-  launch_gemm<1, true, true, 1, 1, EPI_F32>(A, (long long)D.Et * A.n_p_tiles * A.n_q_tiles, st);
+  launch_gemm<1, true, true, 1, 1, EPI_F32>("ffn_bwd_dw_down", A, (long long)D.Et * A.n_p_tiles * A.n_q_tiles, st);
   // dWg[e], dWu[e] = X_e^T dG_e, X_e^T dU_e   (rows d, columns f)
   A.p_dim = D.d; A.n_p_tiles = (D.d + TP - 1) / TP; A.q_dim = D.f; A.n_q_tiles = (D.f + TQ - 1) / TQ;
   A.p0 = x_perm; A.p_ld = D.d;
   A.q0 = dg; A.q1 = du; A.q_ld = D.f;
   A.f0 = dw_gate; A.f1 = dw_up; A.f_expert_stride = (size_t)D.d * D.f; A.c_ld = D.f;
-  launch_gemm<1, true, true, 2, 1, EPI_F32>(A, (long long)D.Et * A.n_p_tiles * A.n_q_tiles, st);
+  launch_gemm<1, true, true, 2, 1, EPI_F32>("ffn_bwd_dw_gate_up", A, (long long)D.Et * A.n_p_tiles * A.n_q_tiles, st);
   return launch_status();
 }

@@ -220,13 +220,13 @@ extern "C" int moe_permute(const moe_shape* shape, const uint16_t* x, const int3
   int nbits = 0;
   while ((1 << nbits) < D.Et) nbits++;
   if (nblk > 0) {
-    hipLaunchKernelGGL(perm_rank_kernel, dim3(nblk), dim3(256), (size_t)kSub * D.Et * sizeof(uint16_t), st, topk_idx, lrank,
+    MOE_LAUNCH("perm_rank", st, perm_rank_kernel, dim3(nblk), dim3(256), (size_t)kSub * D.Et * sizeof(uint16_t), st, topk_idx, lrank,
                        block_hist, (int)D.N, D.Et, nbits);
   }
   // with no slots the scan still defines counts = 0 and offsets = 0
-  hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, st, block_hist, counts, offsets, nblk, D.Et);
+  MOE_LAUNCH("perm_scan", st, perm_scan_kernel, dim3(1), dim3(1024), 0, st, block_hist, counts, offsets, nblk, D.Et);
   if (D.T > 0) {
-    hipLaunchKernelGGL(perm_scatter_kernel, dim3((D.T + 3) / 4), dim3(256), 0, st, reinterpret_cast<const uint4*>(x), topk_idx,
+    MOE_LAUNCH("perm_scatter_gather", st, perm_scatter_kernel, dim3((D.T + 3) / 4), dim3(256), 0, st, reinterpret_cast<const uint4*>(x), topk_idx,
                        lrank, block_hist, reinterpret_cast<uint4*>(x_perm), row_of_slot, slot_of_row, D.T, D.Kp, D.Et, D.d / 8);
   }
   return launch_status();
@@ -241,7 +241,7 @@ extern "C" int moe_permute_bwd(const moe_shape* shape, const uint16_t* dx_perm, 
   MOE_REQUIRE_PTR(dx_perm); MOE_REQUIRE_PTR(row_of_slot); MOE_REQUIRE_PTR(dx);
   MOE_REQUIRE_ALIGNED(dx_perm); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(dx);
   if (D.T == 0) return MOE_OK;
-  hipLaunchKernelGGL((combine_kernel<true>), dim3((D.T + 3) / 4), dim3(256), 0, (hipStream_t)stream,
+  MOE_LAUNCH("permute_bwd", (hipStream_t)stream, (combine_kernel<true>), dim3((D.T + 3) / 4), dim3(256), 0, (hipStream_t)stream,
                      reinterpret_cast<const uint4*>(dx_perm), row_of_slot, (const float*)nullptr, reinterpret_cast<uint4*>(dx),
                      D.T, D.Kp, D.d / 8);
   return launch_status();
@@ -256,7 +256,7 @@ extern "C" int moe_unpermute_combine(const moe_shape* shape, const uint16_t* y_p
   MOE_REQUIRE_PTR(y_perm); MOE_REQUIRE_PTR(row_of_slot); MOE_REQUIRE_PTR(topk_w); MOE_REQUIRE_PTR(out);
   MOE_REQUIRE_ALIGNED(y_perm); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(topk_w); MOE_REQUIRE_ALIGNED(out);
   if (D.T == 0) return MOE_OK;
-  hipLaunchKernelGGL((combine_kernel<false>), dim3((D.T + 3) / 4), dim3(256), 0, (hipStream_t)stream,
+  MOE_LAUNCH("unpermute_combine", (hipStream_t)stream, (combine_kernel<false>), dim3((D.T + 3) / 4), dim3(256), 0, (hipStream_t)stream,
                      reinterpret_cast<const uint4*>(y_perm), row_of_slot, topk_w, reinterpret_cast<uint4*>(out), D.T, D.Kp,
                      D.d / 8);
   return launch_status();
@@ -274,7 +274,7 @@ extern "C" int moe_unpermute_combine_bwd(const moe_shape* shape, const uint16_t*
   MOE_REQUIRE_ALIGNED(dout); MOE_REQUIRE_ALIGNED(y_perm); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(topk_w);
   MOE_REQUIRE_ALIGNED(dy_perm); MOE_REQUIRE_ALIGNED(dtopk_w);
   if (D.T == 0) return MOE_OK;
-  hipLaunchKernelGGL(combine_bwd_kernel, dim3((D.T + 3) / 4), dim3(256), 0, (hipStream_t)stream,
+  MOE_LAUNCH("unpermute_combine_bwd", (hipStream_t)stream, combine_bwd_kernel, dim3((D.T + 3) / 4), dim3(256), 0, (hipStream_t)stream,
                      reinterpret_cast<const uint4*>(dout), reinterpret_cast<const uint4*>(y_perm), row_of_slot, topk_w,
                      reinterpret_cast<uint4*>(dy_perm), dtopk_w, D.T, D.Kp, D.d / 8);
   return launch_status();

@@ -131,7 +131,7 @@ template <int W, int PER>
 static void launch_route(const Dims& D, const float* logits, int32_t* idx, float* w, float* probs, hipStream_t st) {
   int groups_per_block = 256 / W;
   int blocks = (D.T + groups_per_block - 1) / groups_per_block;
-  hipLaunchKernelGGL((route_topk_kernel<W, PER>), dim3(blocks), dim3(256), 0, st, logits, idx, w, probs, D.T, D.E, D.k, D.Es,
+  MOE_LAUNCH("route_topk", st, (route_topk_kernel<W, PER>), dim3(blocks), dim3(256), 0, st, logits, idx, w, probs, D.T, D.E, D.k, D.Es,
                      D.renorm);
 }
 
@@ -171,7 +171,7 @@ extern "C" int moe_route_topk_bwd(const moe_shape* shape, const float* dtopk_w, 
   if (D.T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
 #define MOE_LAUNCH_RBWD(W_)                                                                                              \
-  hipLaunchKernelGGL((route_topk_bwd_kernel<W_>), dim3((D.T + 256 / W_ - 1) / (256 / W_)), dim3(256), 0, st, dtopk_w,   \
+  MOE_LAUNCH("route_topk_bwd", st, (route_topk_bwd_kernel<W_>), dim3((D.T + 256 / W_ - 1) / (256 / W_)), dim3(256), 0, st, dtopk_w,   \
                      topk_idx, topk_w, probs_save, dlogits, D.T, D.E, D.k, D.Es, D.renorm)
   if (D.E <= 8) MOE_LAUNCH_RBWD(8);
   else if (D.E <= 16) MOE_LAUNCH_RBWD(16);
