@@ -48,7 +48,8 @@ class Shape:
 
 
 def library_path() -> str:
-    return os.path.join(PKG_DIR, _LIB_NAME)
+    """The in-tree library; MOE_LIBRARY_PATH overrides it (e.g. to try another build of the same ABI)."""
+    return os.environ.get("MOE_LIBRARY_PATH") or os.path.join(PKG_DIR, _LIB_NAME)
 
 
 def load_library():

@@ -18,7 +18,7 @@ void prof_begin(const char* name, hipStream_t st) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
   ProfRecord r{name, nullptr, nullptr};
   if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
-  hipEventRecord(r.start, st);
+  (void)hipEventRecord(r.start, st);
   g_prof.push_back(r);
   g_prof_open = true;
 }
@@ -27,7 +27,7 @@ void prof_end(hipStream_t st) {
   if (!g_prof_on) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
   if (!g_prof_open || g_prof.empty()) return;
-  hipEventRecord(g_prof.back().stop, st);
+  (void)hipEventRecord(g_prof.back().stop, st);
   g_prof_open = false;
 }
 }  // namespace moe
@@ -56,8 +56,8 @@ extern "C" int moe_profile_get(int i, const char** name, float* ms) {
 extern "C" int moe_profile_reset(void) {
   std::lock_guard<std::mutex> lk(moe::g_prof_mu);
   for (auto& r : moe::g_prof) {
-    hipEventDestroy(r.start);
-    hipEventDestroy(r.stop);
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
   }
   moe::g_prof.clear();
   moe::g_prof_open = false;

@@ -41,11 +41,13 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 //   perm_hist : per-block expert histograms of the counting sort, then turned into per-block bases
 //   perm_rank : rank of every slot among the same-expert slots of its block
 //   sched     : tile schedule of the grouped GEMMs (header + two int arrays)
+//   zero_page : 256 zero bytes, the source of k-rows past the end of a ragged contraction
 //   h, dg, du : bf16 [N,f] intermediates of the expert FFN (H in forward; H, dG, dU in backward)
 struct WsLayout {
   size_t perm_hist, perm_hist_bytes;
   size_t perm_rank, perm_rank_bytes;
   size_t sched, sched_bytes;
+  size_t zero_page;
   size_t h, dg, du, nf_bytes;
   size_t total;
 };
@@ -65,6 +67,8 @@ inline WsLayout ws_layout(const Dims& D) {
   L.sched = off;
   L.sched_bytes = round_up((size_t)(64 + 2 * sched_max_tiles(D)) * sizeof(int32_t), 256);
   off += L.sched_bytes;
+  L.zero_page = off;
+  off += 256;
   L.nf_bytes = round_up((size_t)D.N * D.f * sizeof(uint16_t), 256);
   L.h = off; off += L.nf_bytes;
   L.dg = off; off += L.nf_bytes;

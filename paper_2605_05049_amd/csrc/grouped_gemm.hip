@@ -3,26 +3,29 @@
 // tall-and-skinny GEMMs" of the abstract and Section II-A).
 //
 // One kernel template serves all seven contractions.  Every output tile is
-//     C[p, q] = sum_k  P[p, k] * Q[q, k]          (p: 128 values, q: 128 values, k in steps of 64)
+//     C[p, q] = sum_k  P[p, k] * Q[q, k]          (p: 256 values, q: 256 values, k in steps of 64)
 // where P is the operand whose index becomes the lane-column of the MFMA accumulator and Q the operand whose
 // index becomes the accumulator register (so that each lane owns 4 consecutive q = 4 consecutive output
 // elements of a row-major C).  An operand is "K-contiguous" (KC: element (r,k) at base[r*ld + k]) or
 // "R-contiguous" (RC: element (r,k) at base[k*ld + r]).  KC tiles are read from LDS with 16-byte loads, RC tiles
 // with the gfx950 transposing LDS read (ds_read_b64_tr_b16), so no operand is ever transposed in HBM.
 //
-//   forward   G,U = X Wg, X Wu     P = X (KC)        Q = Wg, Wu (RC)   two accumulators, SwiGLU epilogue
+//   forward   G,U = X Wg, X Wu     P = X (KC)        Q = Wg | Wu (RC)  two 128-wide halves, SwiGLU epilogue
 //             Y   = H Wd           P = H (KC)        Q = Wd (RC)
 //   backward  dH  = dY Wd^T        P = dY (KC)       Q = Wd (KC)       d(SwiGLU) epilogue -> dG, dU, H
 //             dX  = dG Wg^T+dU Wu^T P = dG then dU (KC) Q = Wg then Wu (KC)  one accumulator, two K passes
 //             dWd = H^T dY         P = H (RC)        Q = dY (RC)       ragged K = rows of the expert, fp32 out
-//             dWg,dWu = X^T dG, X^T dU   P = X (RC)  Q = dG, dU (RC)   two accumulators, ragged K, fp32 out
+//             dWg,dWu = X^T dG, X^T dU   P = X (RC)  Q = dG | dU (RC)  two 128-wide halves, ragged K, fp32 out
 //
-// Tiling: 256 threads = 4 wavefronts in a 2x2 grid, each owning 64x64 of the 128x128 tile as 2x2 MFMA
-// 32x32x16 blocks (fp32 accumulators).  Global loads for step k+1 are issued into registers before the MFMAs of
-// step k, then stored to the single LDS stage; two blocks per CU overlap each other's load and math phases.
-// Row tiles of the ragged dimension come from a device-built schedule (no host sync on the counts); the
-// block-id -> tile map hands each XCD a contiguous run of tiles so that tiles sharing a weight panel meet in
-// one L2.
+// Tiling: 512 threads = 8 wavefronts (2 along p x 4 along q); each wavefront owns 128 p x 64 q as 4x2 MFMA
+// 32x32x16 blocks (128 fp32 accumulators per lane).  Tiles stream HBM/L2 -> LDS with the direct 16-byte
+// global->LDS load (no register staging) into two 64 KB stages; step k+1 is in flight while step k is
+// multiplied, one barrier per step.  The LDS destination of a direct load is fixed by the lane id, so bank
+// conflicts are avoided by choosing WHICH 16-byte chunk each lane fetches (an XOR swizzle of the chunk index with
+// row bits), and the fragment reads apply the same swizzle.  Rows past the end of a ragged K (weight gradients)
+// are fetched from a zeroed page.  Row tiles of the ragged dimension come from a device-built schedule (no host
+// sync on the counts); the block-id -> tile map hands each XCD a contiguous run of tiles so that tiles sharing a
+// weight panel meet in one L2.
 #include "common.h"
 
 namespace moe {
@@ -30,87 +33,20 @@ namespace moe {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BK = 64;          // k step
-constexpr int TP = 128;         // p extent of a tile
-constexpr int TQ = 128;         // q extent of a tile
-constexpr int KC_LD = BK + 8;   // LDS row pitch of a K-contiguous tile [128][72]: 16-byte reads hit distinct banks
-constexpr int RC_LD = 128 + 32; // LDS row pitch of an R-contiguous tile [64][160]: 4 k-rows of a transposing read
-                                // land in 4 disjoint bank groups
-constexpr int KC_TILE = 128 * KC_LD;  // elements
-constexpr int RC_TILE = BK * RC_LD;   // elements
+constexpr int BK = 64;                          // k step
+constexpr int TILE = 256;                       // p extent, and (virtual) q extent, of a block tile
+constexpr int NTHREADS = 512;
+constexpr int OPERAND_BYTES = TILE * BK * 2;    // 32 KB per operand per stage
+constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;  // P + Q
+                                                // two stages = 128 KB of the 160 KB of LDS
 constexpr int kNumXcd = 8;
 
 enum Epilogue { EPI_BF16 = 0, EPI_SWIGLU = 1, EPI_DSWIGLU = 2, EPI_F32 = 3 };
 
-// One operand of one tile.
-struct Operand {
-  const uint16_t* base;  // element (r=0, k=0) of the tile
-  size_t ld;             // elements between consecutive r (KC) or consecutive k (RC)
-  int r_valid;           // r in [0, r_valid) exists (1..128); loads beyond are clamped and never stored
-};
-
-template <bool RC>
-__device__ __forceinline__ void load_tile_regs(u32x4 (&reg)[4], const Operand& op, int k0, int k_end, int tid) {
-  if (!RC) {
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      const int v = tid + 256 * i;
-      int r = v >> 3;
-      const int kc = v & 7;
-      r = r < op.r_valid ? r : op.r_valid - 1;
-      reg[i] = *reinterpret_cast<const u32x4*>(op.base + (size_t)r * op.ld + k0 + kc * 8);
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      const int v = tid + 256 * i;
-      const int kr = v >> 4;
-      int c = (v & 15) * 8;
-      c = c < op.r_valid ? c : op.r_valid - 8;
-      const int k = k0 + kr;
-      u32x4 z = {0u, 0u, 0u, 0u};
-      reg[i] = (k < k_end) ? *reinterpret_cast<const u32x4*>(op.base + (size_t)k * op.ld + c) : z;
-    }
-  }
-}
-
-template <bool RC>
-__device__ __forceinline__ void store_tile_lds(const u32x4 (&reg)[4], uint16_t* tile, int tid) {
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const int v = tid + 256 * i;
-    if (!RC) *reinterpret_cast<u32x4*>(tile + (v >> 3) * KC_LD + (v & 7) * 8) = reg[i];
-    else *reinterpret_cast<u32x4*>(tile + (v >> 4) * RC_LD + (v & 15) * 8) = reg[i];
-  }
-}
-
-// MFMA operand fragment: 32 r-values x 16 k-values; lane l gets r = r0 + l%32, k = kk + 8*(l/32) .. +7.
-template <bool RC>
-__device__ __forceinline__ bf16x8 read_frag(const uint16_t* tile, int r0, int kk, int lane) {
-  if (!RC) {
-    return *reinterpret_cast<const bf16x8*>(tile + (r0 + (lane & 31)) * KC_LD + kk + 8 * (lane >> 5));
-  } else {
-    // Transposing read: inside each group of 16 lanes, lane p supplies the address of 4 consecutive r at k-row
-    // p/4, r-chunk p%4, and receives the 4 k-rows of r = (group base) + p.
-    const int p = lane & 15;
-    const uint16_t* a = tile + (kk + 8 * (lane >> 5) + (p >> 2)) * RC_LD + r0 + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
-    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a + 4 * RC_LD));
-    union { struct { s16x4 lo, hi; } s; bf16x8 v; } u;
-    u.s.lo = lo;
-    u.s.hi = hi;
-    return u.v;
-  }
-}
-
-__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
-
 struct GemmArgs {
   // row-tile problems (forward / dgrad): schedule built on the device
-  const int32_t* sched;    // [0] = number of row tiles; then tile_expert[max_tiles], tile_row0[max_tiles]
+  const int32_t* sched;    // [0] = number of row tiles; [64 + u] = expert of tile u; [64 + max_tiles + u] = its first tile
   int max_tiles;
   const int32_t* offsets;  // [E'+1]
   int n_q_tiles;           // tiles along q
@@ -125,26 +61,117 @@ struct GemmArgs {
   int n_p_tiles;
   int Et;
   int accumulate;
+  const uint16_t* zero_page;  // 256 zeroed bytes: source of k-rows past the end of a ragged K
   // outputs
   uint16_t* c0; uint16_t* c1; uint16_t* c2; size_t c_ld;   // bf16 outputs (row-major, ld = q_dim)
   const uint16_t* g_in; const uint16_t* u_in;              // saved G, U for the d(SwiGLU) epilogue
   float* f0; float* f1; size_t f_expert_stride;            // fp32 outputs of the wgrads
 };
 
+// One 256-wide operand of a tile, possibly made of two 128-wide halves from two tensors.
+struct TileOperand {
+  const uint16_t* base0;    // element (r = 0, k = 0) of the first half (or of the whole operand)
+  ptrdiff_t half_delta;     // elements from the first half's origin to the second half's (0 when not split)
+  size_t ld;                // elements between consecutive r (KC) or consecutive k (RC)
+  int r_valid;              // valid r per half (<= 128 when split, <= 256 otherwise); beyond: clamped, never stored
+};
+
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Per-thread source pointers of the 4 direct loads (16 bytes each) that fill this thread's share of one 32 KB
+// operand tile.  Wave w, instruction i fills LDS bytes [(4w+i)*1024, +1024); lane L fills 16 bytes at +16L.
+//   KC: LDS row r (128 bytes) = 8 chunks of 8 k-values; chunk c sits at position c ^ ((r >> 1) & 7).
+//   RC: LDS k-row (512 bytes) = 32 chunks of 8 r-values; chunk c sits at position c ^ ((k & 3) << 2).
+template <bool RC, bool SPLIT>
+__device__ __forceinline__ void tile_sources(const uint16_t* (&src)[4], int (&krow)[4], const TileOperand& op, int tid) {
+  const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int inst = wave * 4 + i;
+    if (!RC) {
+      const int r = inst * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      const int half = SPLIT ? (r >> 7) : 0;
+      int rr = SPLIT ? (r & 127) : r;
+      rr = rr < op.r_valid ? rr : op.r_valid - 1;
+      src[i] = op.base0 + (half ? op.half_delta : (ptrdiff_t)0) + (size_t)rr * op.ld + c * 8;
+      krow[i] = 0;
+    } else {
+      const int kr = inst * 2 + (lane >> 5);
+      const int c = (lane & 31) ^ ((kr & 3) << 2);
+      const int half = SPLIT ? (c >> 4) : 0;
+      int col = SPLIT ? (c & 15) * 8 : c * 8;
+      col = col < op.r_valid ? col : op.r_valid - 8;
+      src[i] = op.base0 + (half ? op.half_delta : (ptrdiff_t)0) + (size_t)kr * op.ld + col;
+      krow[i] = kr;
+    }
+  }
+}
+
+// One direct global->LDS load: 16 bytes per lane, lane L lands at lds_base + 16 L (lds_base is wave-uniform).
+// Written as inline assembly on purpose: the compiler does not track it, so it never makes the (transposing)
+// fragment reads of the OTHER stage wait for loads still in flight.  The kernel orders these loads itself: an
+// explicit s_waitcnt vmcnt(0) precedes the barrier that publishes a stage, and no compiler-tracked vector-memory
+// load is in flight while these are (the epilogue starts after the last such wait).
+__device__ __forceinline__ void direct_load16(const void* g, const char* lds_dst) {
+  const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)lds_dst);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(g) : "memory");
+}
+
+// Issues this thread's 4 direct global->LDS loads of one operand tile for the k-step starting at k0.
+template <bool RC>
+__device__ __forceinline__ void issue_tile(const uint16_t* const (&src)[4], const int (&krow)[4], size_t ld, int k0, int k_end,
+                                           const uint16_t* zero_page, char* lds_tile, int tid) {
+  char* dst = lds_tile + (tid >> 6) * 4096;  // this wavefront's 4 KB of the tile
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const uint16_t* g;
+    if (!RC) g = src[i] + k0;
+    else g = (k0 + krow[i] < k_end) ? src[i] + (size_t)k0 * ld : zero_page;
+    direct_load16(g, dst + i * 1024);
+  }
+}
+
+// MFMA operand fragment: 32 r-values x 16 k-values; lane l gets r = r0 + l%32, k = kk + 8*(l/32) .. +7.
+template <bool RC>
+__device__ __forceinline__ bf16x8 read_frag(const char* tile, int r0, int kk, int lane) {
+  if (!RC) {
+    const int r = r0 + (lane & 31);
+    const int c = (kk >> 3) + (lane >> 5);
+    return *reinterpret_cast<const bf16x8*>(tile + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
+  } else {
+    // Transposing read: inside each group of 16 lanes, lane p supplies the address of 4 consecutive r at k-row
+    // p/4, r-chunk p%4, and receives the 4 k-rows of r = (group base) + p.
+    const int p = lane & 15;
+    const int k = kk + 8 * (lane >> 5) + (p >> 2);
+    const int relem = r0 + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
+    const int c = relem >> 3;
+    const char* a = tile + k * 512 + ((c ^ ((k & 3) << 2)) << 4) + ((relem & 7) << 1);
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a + 4 * 512));
+    union { struct { s16x4 lo, hi; } s; bf16x8 v; } u;
+    u.s.lo = lo;
+    u.s.hi = hi;
+    return u.v;
+  }
+}
+
 // KIND 0: row-tile problem (p = ragged rows of an expert, k = k_dim);  KIND 1: wgrad (k = ragged rows).
+// NQ = 2: the q tile is two 128-wide halves from q0 and q1 (acc[0] = q0 result, acc[1] = q1 result at the same q).
 template <int KIND, bool P_RC, bool Q_RC, int NQ, int NPASS, int EPI>
-__global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(const GemmArgs A) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  constexpr int P_TILE = P_RC ? RC_TILE : KC_TILE;
-  constexpr int Q_TILE = Q_RC ? RC_TILE : KC_TILE;
-  uint16_t* p_lds = smem;
-  uint16_t* q_lds = smem + P_TILE;
+__global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A) {
+  // Two stages as two distinct arrays: the compiler can then tell that a direct load into one stage does not
+  // alias the fragment reads of the other, and does not make those reads wait for the load.
+  __shared__ __attribute__((aligned(1024))) char stage0[STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char stage1[STAGE_BYTES];
+  constexpr int TQ = TILE / NQ;  // q extent per output tensor
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int wp = (wave & 1) * 64;
-  const int wq = (wave >> 1) * 64;
+  const int wp = (wave & 1) * 128;  // p origin of this wavefront
+  const int wq = wave >> 1;         // 0..3 along q
 
   // ---- block id -> tile (each XCD takes a contiguous run of the logical tile order) ----
   int expert, p_row0 = 0, p_valid, q0_col, k_len;
@@ -159,13 +186,13 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(const GemmArgs A) 
     const int u = (int)(lid / A.n_q_tiles);  // some row tile of the expert this block works for
     expert = A.sched[64 + u];
     const int e_lo = A.offsets[expert], e_hi = A.offsets[expert + 1];
-    const int e_tiles = (e_hi - e_lo + TP - 1) / TP;
+    const int e_tiles = (e_hi - e_lo + TILE - 1) / TILE;
     const int first = A.sched[64 + A.max_tiles + u];  // index of the expert's first row tile
     const long long local = lid - (long long)first * A.n_q_tiles;
     const int qt = (int)(local / e_tiles);
     const int mt = (int)(local % e_tiles);
-    p_row0 = e_lo + mt * TP;
-    p_valid = min(TP, e_hi - p_row0);
+    p_row0 = e_lo + mt * TILE;
+    p_valid = min(TILE, e_hi - p_row0);
     q0_col = qt * TQ;
     k_len = A.k_dim;
   } else {
@@ -182,109 +209,111 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(const GemmArgs A) 
     const int e_lo = A.offsets[expert], e_hi = A.offsets[expert + 1];
     k_len = e_hi - e_lo;
     krow0 = (size_t)e_lo;
-    p_row0 = pt * TP;
-    p_valid = min(TP, A.p_dim - p_row0);
+    p_row0 = pt * TILE;
+    p_valid = min(TILE, A.p_dim - p_row0);
     q0_col = qt * TQ;
     if (k_len == 0 && A.accumulate) return;  // nothing to add
   }
   const int q_valid = min(TQ, A.q_dim - q0_col);
 
-  f32x16 acc[NQ][2][2];
-#pragma unroll
-  for (int n = 0; n < NQ; n++)
-#pragma unroll
-    for (int a = 0; a < 2; a++)
-#pragma unroll
-      for (int b = 0; b < 2; b++)
-#pragma unroll
-        for (int v = 0; v < 16; v++) acc[n][a][b][v] = 0.f;
-
-#pragma unroll
-  for (int pass = 0; pass < NPASS; pass++) {
-    Operand P, Q[NQ];
-    if (KIND == 0) {
-      const uint16_t* pb = (pass == 0) ? A.p0 : A.p1;
-      P.base = pb + (size_t)p_row0 * A.p_ld;
-      P.ld = A.p_ld;
-      P.r_valid = p_valid;
-#pragma unroll
-      for (int n = 0; n < NQ; n++) {
-        // one accumulator, two passes: pass selects the weight; two accumulators: n selects it
-        const uint16_t* qb = ((NPASS == 2 ? pass : n) == 0) ? A.q0 : A.q1;
-        qb += (size_t)expert * A.q_expert_stride;
-        Q[n].base = Q_RC ? qb + q0_col : qb + (size_t)q0_col * A.q_ld;
-        Q[n].ld = A.q_ld;
-        Q[n].r_valid = q_valid;
-      }
-    } else {
-      P.base = A.p0 + krow0 * A.p_ld + p_row0;
-      P.ld = A.p_ld;
-      P.r_valid = p_valid;
-#pragma unroll
-      for (int n = 0; n < NQ; n++) {
-        const uint16_t* qb = (n == 0) ? A.q0 : A.q1;
-        Q[n].base = qb + krow0 * A.q_ld + q0_col;
-        Q[n].ld = A.q_ld;
-        Q[n].r_valid = q_valid;
-      }
-    }
-
-    const int nk = (k_len + BK - 1) / BK;
-    u32x4 preg[4], qreg[NQ][4];
-    if (nk > 0) {
-      load_tile_regs<P_RC>(preg, P, 0, k_len, tid);
-#pragma unroll
-      for (int n = 0; n < NQ; n++) load_tile_regs<Q_RC>(qreg[n], Q[n], 0, k_len, tid);
-    }
-    for (int kt = 0; kt < nk; kt++) {
-      __syncthreads();  // everyone has finished reading the previous stage
-      store_tile_lds<P_RC>(preg, p_lds, tid);
-#pragma unroll
-      for (int n = 0; n < NQ; n++) store_tile_lds<Q_RC>(qreg[n], q_lds + n * Q_TILE, tid);
-      __syncthreads();
-      if (kt + 1 < nk) {
-        load_tile_regs<P_RC>(preg, P, (kt + 1) * BK, k_len, tid);
-#pragma unroll
-        for (int n = 0; n < NQ; n++) load_tile_regs<Q_RC>(qreg[n], Q[n], (kt + 1) * BK, k_len, tid);
-      }
-#pragma unroll
-      for (int kk = 0; kk < BK; kk += 16) {
-        bf16x8 pf[2], qf[NQ][2];
-#pragma unroll
-        for (int b = 0; b < 2; b++) pf[b] = read_frag<P_RC>(p_lds, wp + 32 * b, kk, lane);
-#pragma unroll
-        for (int n = 0; n < NQ; n++)
-#pragma unroll
-          for (int a = 0; a < 2; a++) qf[n][a] = read_frag<Q_RC>(q_lds + n * Q_TILE, wq + 32 * a, kk, lane);
-#pragma unroll
-        for (int n = 0; n < NQ; n++)
-#pragma unroll
-          for (int a = 0; a < 2; a++)
-#pragma unroll
-            for (int b = 0; b < 2; b++)
-              acc[n][a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[n][a], pf[b], acc[n][a][b], 0, 0, 0);
-      }
-    }
-  }
-
-  // ---- epilogue.  acc[n][a][b][v]: q = wq + 32a + 8(v/4) + 4(lane/32) + v%4,  p = wp + 32b + lane%32 ----
+  f32x16 acc[2][4];  // [q sub-tile a][p sub-tile b]
 #pragma unroll
   for (int a = 0; a < 2; a++)
 #pragma unroll
-    for (int b = 0; b < 2; b++) {
-      const int p = wp + 32 * b + (lane & 31);
-      if (p >= p_valid) continue;
+    for (int b = 0; b < 4; b++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[a][b][v] = 0.f;
+
+  // LDS row origin of this wavefront's two q fragments
+  const int qr0 = (NQ == 2) ? wq * 32 : wq * 64;
+  const int qr1 = (NQ == 2) ? 128 + wq * 32 : wq * 64 + 32;
+
+#pragma unroll
+  for (int pass = 0; pass < NPASS; pass++) {
+    TileOperand P, Q;
+    if (KIND == 0) {
+      const uint16_t* pb = (pass == 0) ? A.p0 : A.p1;
+      P.base0 = pb + (size_t)p_row0 * A.p_ld;
+      P.half_delta = 0;
+      P.ld = A.p_ld;
+      P.r_valid = p_valid;
+      const uint16_t* qa = ((NPASS == 2 && pass == 1) ? A.q1 : A.q0) + (size_t)expert * A.q_expert_stride;
+      const uint16_t* qb = (NQ == 2) ? A.q1 + (size_t)expert * A.q_expert_stride : qa;
+      Q.base0 = Q_RC ? qa + q0_col : qa + (size_t)q0_col * A.q_ld;
+      Q.half_delta = qb - qa;
+      Q.ld = A.q_ld;
+      Q.r_valid = q_valid;
+    } else {
+      P.base0 = A.p0 + krow0 * A.p_ld + p_row0;
+      P.half_delta = 0;
+      P.ld = A.p_ld;
+      P.r_valid = p_valid;
+      Q.base0 = A.q0 + krow0 * A.q_ld + q0_col;
+      Q.half_delta = (NQ == 2) ? A.q1 - A.q0 : (ptrdiff_t)0;
+      Q.ld = A.q_ld;
+      Q.r_valid = q_valid;
+    }
+    const uint16_t* psrc[4];
+    const uint16_t* qsrc[4];
+    int pk[4], qk[4];
+    tile_sources<P_RC, false>(psrc, pk, P, tid);
+    tile_sources<Q_RC, NQ == 2>(qsrc, qk, Q, tid);
+
+    const int nk = (k_len + BK - 1) / BK;
+    if (pass > 0) __syncthreads();  // the previous pass has finished reading both stages
+    if (nk > 0) {
+      issue_tile<P_RC>(psrc, pk, P.ld, 0, k_len, A.zero_page, stage0, tid);
+      issue_tile<Q_RC>(qsrc, qk, Q.ld, 0, k_len, A.zero_page, stage0 + OPERAND_BYTES, tid);
+    }
+    // one k-step: wait for stage `cur`, start filling `nxt` with step kt+1, multiply `cur`
+    auto k_step = [&](const char* cur, char* nxt, int kt) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this thread's loads of step kt have landed in LDS
+      __syncthreads();                     // ... and everyone's; everyone is also done reading the other stage
+      if (kt + 1 < nk) {
+        issue_tile<P_RC>(psrc, pk, P.ld, (kt + 1) * BK, k_len, A.zero_page, nxt, tid);
+        issue_tile<Q_RC>(qsrc, qk, Q.ld, (kt + 1) * BK, k_len, A.zero_page, nxt + OPERAND_BYTES, tid);
+      }
+      const char* p_lds = cur;
+      const char* q_lds = cur + OPERAND_BYTES;
+#pragma unroll
+      for (int kk = 0; kk < BK; kk += 16) {
+        bf16x8 pf[4], qf[2];
+        qf[0] = read_frag<Q_RC>(q_lds, qr0, kk, lane);
+        qf[1] = read_frag<Q_RC>(q_lds, qr1, kk, lane);
+#pragma unroll
+        for (int b = 0; b < 4; b++) pf[b] = read_frag<P_RC>(p_lds, wp + 32 * b, kk, lane);
+#pragma unroll
+        for (int b = 0; b < 4; b++)
+#pragma unroll
+          for (int a = 0; a < 2; a++)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[a], pf[b], acc[a][b], 0, 0, 0);
+      }
+    };
+    for (int kt = 0; kt < nk; kt += 2) {
+      k_step(stage0, stage1, kt);
+      if (kt + 1 < nk) k_step(stage1, stage0, kt + 1);
+    }
+  }
+
+  // ---- epilogue.  acc[a][b][v]: p = wp + 32b + lane%32;  q (inside the output's tile) =
+  //      NQ == 1: 64 wq + 32a + 8(v/4) + 4(lane/32) + v%4      NQ == 2: 32 wq + 8(v/4) + 4(lane/32) + v%4, output a
+#pragma unroll
+  for (int b = 0; b < 4; b++) {
+    const int p = wp + 32 * b + (lane & 31);
+    if (p >= p_valid) continue;
+#pragma unroll
+    for (int a = 0; a < (NQ == 2 ? 1 : 2); a++)
 #pragma unroll
       for (int v4 = 0; v4 < 4; v4++) {
-        const int q = wq + 32 * a + 8 * v4 + 4 * (lane >> 5);
+        const int q = (NQ == 2 ? wq * 32 : wq * 64 + 32 * a) + 8 * v4 + 4 * (lane >> 5);
         if (q >= q_valid) continue;
         if (EPI == EPI_F32) {
           const size_t o = (size_t)expert * A.f_expert_stride + (size_t)(p_row0 + p) * A.c_ld + q0_col + q;
 #pragma unroll
           for (int n = 0; n < NQ; n++) {
+            const int ai = (NQ == 2) ? n : a;
             float* dst = (n == 0 ? A.f0 : A.f1) + o;
-            float4 r = make_float4(acc[n][a][b][4 * v4], acc[n][a][b][4 * v4 + 1], acc[n][a][b][4 * v4 + 2],
-                                   acc[n][a][b][4 * v4 + 3]);
+            float4 r = make_float4(acc[ai][b][4 * v4], acc[ai][b][4 * v4 + 1], acc[ai][b][4 * v4 + 2], acc[ai][b][4 * v4 + 3]);
             if (A.accumulate) {
               const float4 old = *reinterpret_cast<const float4*>(dst);
               r.x += old.x; r.y += old.y; r.z += old.z; r.w += old.w;
@@ -295,16 +324,16 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(const GemmArgs A) 
           const size_t o = (size_t)(p_row0 + p) * A.c_ld + q0_col + q;
           if (EPI == EPI_BF16) {
             uint2 r;
-            r.x = pack_bf16(acc[0][a][b][4 * v4], acc[0][a][b][4 * v4 + 1]);
-            r.y = pack_bf16(acc[0][a][b][4 * v4 + 2], acc[0][a][b][4 * v4 + 3]);
+            r.x = pack_bf16(acc[a][b][4 * v4], acc[a][b][4 * v4 + 1]);
+            r.y = pack_bf16(acc[a][b][4 * v4 + 2], acc[a][b][4 * v4 + 3]);
             *reinterpret_cast<uint2*>(A.c0 + o) = r;
-          } else if (EPI == EPI_SWIGLU) {
+          } else if (EPI == EPI_SWIGLU) {  // NQ == 2: acc[0] = G, acc[1] = U
             float g[4], u[4], h[4];
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-              g[i] = acc[0][a][b][4 * v4 + i];
-              u[i] = acc[NQ - 1][a][b][4 * v4 + i];
-              h[i] = silu_f(g[i]) * u[i];
+              g[i] = acc[0][b][4 * v4 + i];
+              u[i] = acc[1][b][4 * v4 + i];
+              h[i] = g[i] / (1.0f + __expf(-g[i])) * u[i];
             }
             *reinterpret_cast<uint2*>(A.c0 + o) = make_uint2(pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3]));
             *reinterpret_cast<uint2*>(A.c1 + o) = make_uint2(pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3]));
@@ -317,7 +346,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(const GemmArgs A) 
             float dg[4], du[4], h[4];
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-              const float dh = acc[0][a][b][4 * v4 + i];
+              const float dh = acc[a][b][4 * v4 + i];
               const float s = 1.0f / (1.0f + __expf(-g[i]));
               const float sl = g[i] * s;
               h[i] = sl * u[i];
@@ -330,17 +359,18 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(const GemmArgs A) 
           }
         }
       }
-    }
+  }
 }
 
-// Row-tile schedule: one thread per expert.  sched[0] = number of 128-row tiles; sched[64 + u] = expert of tile u;
-// sched[64 + max_tiles + u] = index of that expert's first tile.
+// Row-tile schedule: one thread per expert.  sched[0] = number of 256-row tiles; sched[64 + u] = expert of tile u;
+// sched[64 + max_tiles + u] = index of that expert's first tile.  The first 64 threads also clear the zero page.
 __global__ __launch_bounds__(1024) void build_schedule_kernel(const int32_t* __restrict__ offsets, int32_t* __restrict__ sched,
-                                                              int Et, int max_tiles) {
+                                                              uint32_t* __restrict__ zero_page, int Et, int max_tiles) {
   __shared__ int32_t scan[kMaxExperts];
   const int e = threadIdx.x;
+  if (e < 64) zero_page[e] = 0u;
   const int n = (e < Et) ? offsets[e + 1] - offsets[e] : 0;
-  const int nt = (n + TP - 1) / TP;
+  const int nt = (n + TILE - 1) / TILE;
   scan[e] = nt;
   __syncthreads();
   for (int o = 1; o < kMaxExperts; o <<= 1) {
@@ -360,11 +390,12 @@ __global__ __launch_bounds__(1024) void build_schedule_kernel(const int32_t* __r
 }
 
 template <int KIND, bool P_RC, bool Q_RC, int NQ, int NPASS, int EPI>
-static void launch_gemm(const char* label, const GemmArgs& A, long long max_blocks, hipStream_t st) {
-  constexpr size_t lds = ((P_RC ? RC_TILE : KC_TILE) + NQ * (Q_RC ? RC_TILE : KC_TILE)) * sizeof(uint16_t);
+static int launch_gemm(const char* label, const GemmArgs& A, long long max_blocks, hipStream_t st) {
+  auto kern = grouped_gemm_kernel<KIND, P_RC, Q_RC, NQ, NPASS, EPI>;
   const long long grid = (max_blocks + kNumXcd - 1) / kNumXcd * kNumXcd;
-  if (grid <= 0) return;
-  MOE_LAUNCH(label, st, (grouped_gemm_kernel<KIND, P_RC, Q_RC, NQ, NPASS, EPI>), dim3((unsigned)grid), dim3(256), lds, st, A);
+  if (grid <= 0) return MOE_OK;
+  MOE_LAUNCH(label, st, kern, dim3((unsigned)grid), dim3(NTHREADS), 0, st, A);
+  return MOE_OK;
 }
 
 static int common_checks(const moe_shape* shape, Dims* D, void* ws, size_t ws_bytes, WsLayout* L) {
@@ -376,6 +407,8 @@ static int common_checks(const moe_shape* shape, Dims* D, void* ws, size_t ws_by
   if (ws_bytes < L->total) return MOE_ERR_WORKSPACE;
   return MOE_OK;
 }
+
+#define MOE_TRY(call) do { int rc_ = (call); if (rc_ != MOE_OK) return rc_; } while (0)
 
 }  // namespace moe
 
@@ -396,25 +429,27 @@ extern "C" int moe_grouped_ffn_fwd(const moe_shape* shape, const uint16_t* x_per
   hipStream_t st = (hipStream_t)stream;
   char* wsb = static_cast<char*>(ws);
   int32_t* sched = reinterpret_cast<int32_t*>(wsb + L.sched);
+  uint32_t* zero_page = reinterpret_cast<uint32_t*>(wsb + L.zero_page);
   uint16_t* h = reinterpret_cast<uint16_t*>(wsb + L.h);
   const int max_tiles = (int)sched_max_tiles(D);
-  const long long ub_tiles = D.N / TP + D.Et;  // sum_e ceil(n_e/128) <= N/128 + E'
-  MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, D.Et, max_tiles);
+  const long long ub_tiles = D.N / TILE + D.Et;  // sum_e ceil(n_e/256) <= N/256 + E'
+  MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, D.Et, max_tiles);
 
   GemmArgs A = {};
   A.sched = sched; A.max_tiles = max_tiles; A.offsets = offsets; A.Et = D.Et;
+  A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
   // G, U = X Wg, X Wu ; H = silu(G) * U
-  A.n_q_tiles = (D.f + TQ - 1) / TQ; A.q_dim = D.f; A.k_dim = D.d;
+  A.n_q_tiles = (D.f + 127) / 128; A.q_dim = D.f; A.k_dim = D.d;
   A.p0 = x_perm; A.p_ld = D.d;
   A.q0 = w_gate; A.q1 = w_up; A.q_ld = D.f; A.q_expert_stride = (size_t)D.d * D.f;
   A.c0 = save_g; A.c1 = save_u; A.c2 = h; A.c_ld = D.f;
-  launch_gemm<0, false, true, 2, 1, EPI_SWIGLU>("ffn_fwd_gate_up_swiglu", A, ub_tiles * A.n_q_tiles, st);
+  MOE_TRY((launch_gemm<0, false, true, 2, 1, EPI_SWIGLU>("ffn_fwd_gate_up_swiglu", A, ub_tiles * A.n_q_tiles, st)));
   // Y = H Wd
-  A.n_q_tiles = (D.d + TQ - 1) / TQ; A.q_dim = D.d; A.k_dim = D.f;
+  A.n_q_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.d; A.k_dim = D.f;
   A.p0 = h; A.p_ld = D.f;
   A.q0 = w_down; A.q1 = nullptr; A.q_ld = D.d; A.q_expert_stride = (size_t)D.f * D.d;
   A.c0 = y_perm; A.c1 = nullptr; A.c2 = nullptr; A.c_ld = D.d;
-  launch_gemm<0, false, true, 1, 1, EPI_BF16>("ffn_fwd_down", A, ub_tiles * A.n_q_tiles, st);
+  MOE_TRY((launch_gemm<0, false, true, 1, 1, EPI_BF16>("ffn_fwd_down", A, ub_tiles * A.n_q_tiles, st)));
   return launch_status();
 }
 
@@ -437,40 +472,42 @@ extern "C" int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_pe
   hipStream_t st = (hipStream_t)stream;
   char* wsb = static_cast<char*>(ws);
   int32_t* sched = reinterpret_cast<int32_t*>(wsb + L.sched);
+  uint32_t* zero_page = reinterpret_cast<uint32_t*>(wsb + L.zero_page);
   uint16_t* h = reinterpret_cast<uint16_t*>(wsb + L.h);
   uint16_t* dg = reinterpret_cast<uint16_t*>(wsb + L.dg);
   uint16_t* du = reinterpret_cast<uint16_t*>(wsb + L.du);
   const int max_tiles = (int)sched_max_tiles(D);
-  const long long ub_tiles = D.N / TP + D.Et;
+  const long long ub_tiles = D.N / TILE + D.Et;
 
   GemmArgs A = {};
   A.sched = sched; A.max_tiles = max_tiles; A.offsets = offsets; A.Et = D.Et; A.accumulate = accumulate ? 1 : 0;
+  A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
   if (D.N > 0) {
-    MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, D.Et, max_tiles);
+    MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, D.Et, max_tiles);
     // dH = dY Wd^T, then dG, dU and H from the saved G, U
-    A.n_q_tiles = (D.f + TQ - 1) / TQ; A.q_dim = D.f; A.k_dim = D.d;
+    A.n_q_tiles = (D.f + TILE - 1) / TILE; A.q_dim = D.f; A.k_dim = D.d;
     A.p0 = dy_perm; A.p_ld = D.d;
     A.q0 = w_down; A.q_ld = D.d; A.q_expert_stride = (size_t)D.f * D.d;
     A.c0 = dg; A.c1 = du; A.c2 = h; A.c_ld = D.f; A.g_in = save_g; A.u_in = save_u;
-    launch_gemm<0, false, false, 1, 1, EPI_DSWIGLU>("ffn_bwd_dh_dswiglu", A, ub_tiles * A.n_q_tiles, st);
+    MOE_TRY((launch_gemm<0, false, false, 1, 1, EPI_DSWIGLU>("ffn_bwd_dh_dswiglu", A, ub_tiles * A.n_q_tiles, st)));
     // dX = dG Wg^T + dU Wu^T
-    A.n_q_tiles = (D.d + TQ - 1) / TQ; A.q_dim = D.d; A.k_dim = D.f;
+    A.n_q_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.d; A.k_dim = D.f;
     A.p0 = dg; A.p1 = du; A.p_ld = D.f;
     A.q0 = w_gate; A.q1 = w_up; A.q_ld = D.f; A.q_expert_stride = (size_t)D.d * D.f;
     A.c0 = dx_perm; A.c1 = nullptr; A.c2 = nullptr; A.c_ld = D.d;
-    launch_gemm<0, false, false, 1, 2, EPI_BF16>("ffn_bwd_dx", A, ub_tiles * A.n_q_tiles, st);
+    MOE_TRY((launch_gemm<0, false, false, 1, 2, EPI_BF16>("ffn_bwd_dx", A, ub_tiles * A.n_q_tiles, st)));
   }
   // dWd[e] = H_e^T dY_e   (rows f, columns d)
-  A.p_dim = D.f; A.n_p_tiles = (D.f + TP - 1) / TP; A.q_dim = D.d; A.n_q_tiles = (D.d + TQ - 1) / TQ;
+  A.p_dim = D.f; A.n_p_tiles = (D.f + TILE - 1) / TILE; A.q_dim = D.d; A.n_q_tiles = (D.d + TILE - 1) / TILE;
   A.p0 = h; A.p1 = nullptr; A.p_ld = D.f;
   A.q0 = dy_perm; A.q1 = nullptr; A.q_ld = D.d;
   A.f0 = dw_down; A.f1 = nullptr; A.f_expert_stride = (size_t)D.f * D.d; A.c_ld = D.d;
-  launch_gemm<1, true, true, 1, 1, EPI_F32>("ffn_bwd_dw_down", A, (long long)D.Et * A.n_p_tiles * A.n_q_tiles, st);
+  MOE_TRY((launch_gemm<1, true, true, 1, 1, EPI_F32>("ffn_bwd_dw_down", A, (long long)D.Et * A.n_p_tiles * A.n_q_tiles, st)));
   // dWg[e], dWu[e] = X_e^T dG_e, X_e^T dU_e   (rows d, columns f)
-  A.p_dim = D.d; A.n_p_tiles = (D.d + TP - 1) / TP; A.q_dim = D.f; A.n_q_tiles = (D.f + TQ - 1) / TQ;
+  A.p_dim = D.d; A.n_p_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.f; A.n_q_tiles = (D.f + 127) / 128;
   A.p0 = x_perm; A.p_ld = D.d;
   A.q0 = dg; A.q1 = du; A.q_ld = D.f;
   A.f0 = dw_gate; A.f1 = dw_up; A.f_expert_stride = (size_t)D.d * D.f; A.c_ld = D.f;
-  launch_gemm<1, true, true, 2, 1, EPI_F32>("ffn_bwd_dw_gate_up", A, (long long)D.Et * A.n_p_tiles * A.n_q_tiles, st);
+  MOE_TRY((launch_gemm<1, true, true, 2, 1, EPI_F32>("ffn_bwd_dw_gate_up", A, (long long)D.Et * A.n_p_tiles * A.n_q_tiles, st)));
   return launch_status();
 }
