@@ -295,70 +295,109 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     }
   }
 
-  // ---- epilogue.  acc[a][b][v]: p = wp + 32b + lane%32;  q (inside the output's tile) =
-  //      NQ == 1: 64 wq + 32a + 8(v/4) + 4(lane/32) + v%4      NQ == 2: 32 wq + 8(v/4) + 4(lane/32) + v%4, output a
+  // ---- epilogue.  acc[a][b][v] holds  p = wp + 32b + lane%32,  q (inside the output's tile) =
+  //      NQ == 1: 64 wq + 32a + 8(v/4) + 4(lane/32) + v%4      NQ == 2: 32 wq + 8(v/4) + 4(lane/32) + v%4 of output a.
+  // Lanes 0..31 of an accumulator own 32 different rows, so storing from the accumulators would touch 64 cache lines
+  // per instruction.  Instead each wavefront bounces 32 rows at a time through its own 16 KB of the (now idle) LDS
+  // and reads them back row-wise: every global access is then 16 bytes per lane over 64..256 contiguous bytes per row,
+  // and the SwiGLU element-wise math runs on that side (8 consecutive q per lane).
+  constexpr int W = (NQ == 2) ? 32 : 64;       // q extent this wavefront owns per output tensor
+  constexpr int PITCH = W * 4 + 16;            // bytes per staged fp32 row; the +16 keeps 16-byte accesses conflict-free
+  __syncthreads();                             // every wavefront has finished reading the stages
+  char* wlds = ((wave < 4) ? stage0 : stage1) + (wave & 3) * 16384;
+  const int q_base = wq * W;                   // first q of this wavefront inside the output's tile
 #pragma unroll
   for (int b = 0; b < 4; b++) {
-    const int p = wp + 32 * b + (lane & 31);
-    if (p >= p_valid) continue;
+    // registers -> LDS (fp32), 32 rows x W columns per output tensor (second tensor at +8 KB when NQ == 2)
 #pragma unroll
-    for (int a = 0; a < (NQ == 2 ? 1 : 2); a++)
+    for (int a = 0; a < 2; a++)
 #pragma unroll
       for (int v4 = 0; v4 < 4; v4++) {
-        const int q = (NQ == 2 ? wq * 32 : wq * 64 + 32 * a) + 8 * v4 + 4 * (lane >> 5);
-        if (q >= q_valid) continue;
-        if (EPI == EPI_F32) {
-          const size_t o = (size_t)expert * A.f_expert_stride + (size_t)(p_row0 + p) * A.c_ld + q0_col + q;
+        const int q = (NQ == 2 ? 0 : 32 * a) + 8 * v4 + 4 * (lane >> 5);
+        float4 r = make_float4(acc[a][b][4 * v4], acc[a][b][4 * v4 + 1], acc[a][b][4 * v4 + 2], acc[a][b][4 * v4 + 3]);
+        *reinterpret_cast<float4*>(wlds + (NQ == 2 ? a * 8192 : 0) + (lane & 31) * PITCH + q * 4) = r;
+      }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wavefront's own LDS writes are done
+    __builtin_amdgcn_wave_barrier();
+    if (EPI == EPI_F32) {
+      // 4 q per lane (16 bytes of fp32)
+      constexpr int LPR = W / 4;          // lanes per row
+      constexpr int RPI = 64 / LPR;       // rows per instruction
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; it++) {
+        const int r = it * RPI + lane / LPR;
+        const int q = (lane % LPR) * 4;
+        const int p = wp + 32 * b + r;
+        if (p < p_valid && q_base + q < q_valid) {
+          const size_t o = (size_t)expert * A.f_expert_stride + (size_t)(p_row0 + p) * A.c_ld + q0_col + q_base + q;
 #pragma unroll
           for (int n = 0; n < NQ; n++) {
-            const int ai = (NQ == 2) ? n : a;
+            float4 v = *reinterpret_cast<const float4*>(wlds + n * 8192 + r * PITCH + q * 4);
             float* dst = (n == 0 ? A.f0 : A.f1) + o;
-            float4 r = make_float4(acc[ai][b][4 * v4], acc[ai][b][4 * v4 + 1], acc[ai][b][4 * v4 + 2], acc[ai][b][4 * v4 + 3]);
             if (A.accumulate) {
               const float4 old = *reinterpret_cast<const float4*>(dst);
-              r.x += old.x; r.y += old.y; r.z += old.z; r.w += old.w;
+              v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
             }
-            *reinterpret_cast<float4*>(dst) = r;
-          }
-        } else {
-          const size_t o = (size_t)(p_row0 + p) * A.c_ld + q0_col + q;
-          if (EPI == EPI_BF16) {
-            uint2 r;
-            r.x = pack_bf16(acc[a][b][4 * v4], acc[a][b][4 * v4 + 1]);
-            r.y = pack_bf16(acc[a][b][4 * v4 + 2], acc[a][b][4 * v4 + 3]);
-            *reinterpret_cast<uint2*>(A.c0 + o) = r;
-          } else if (EPI == EPI_SWIGLU) {  // NQ == 2: acc[0] = G, acc[1] = U
-            float g[4], u[4], h[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-              g[i] = acc[0][b][4 * v4 + i];
-              u[i] = acc[1][b][4 * v4 + i];
-              h[i] = g[i] / (1.0f + __expf(-g[i])) * u[i];
-            }
-            *reinterpret_cast<uint2*>(A.c0 + o) = make_uint2(pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3]));
-            *reinterpret_cast<uint2*>(A.c1 + o) = make_uint2(pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3]));
-            *reinterpret_cast<uint2*>(A.c2 + o) = make_uint2(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]));
-          } else {  // EPI_DSWIGLU: acc = dH; read saved G, U; write dG, dU, H
-            const uint2 gi = *reinterpret_cast<const uint2*>(A.g_in + o);
-            const uint2 ui = *reinterpret_cast<const uint2*>(A.u_in + o);
-            const float g[4] = {bf16lo(gi.x), bf16hi(gi.x), bf16lo(gi.y), bf16hi(gi.y)};
-            const float u[4] = {bf16lo(ui.x), bf16hi(ui.x), bf16lo(ui.y), bf16hi(ui.y)};
-            float dg[4], du[4], h[4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-              const float dh = acc[a][b][4 * v4 + i];
-              const float s = 1.0f / (1.0f + __expf(-g[i]));
-              const float sl = g[i] * s;
-              h[i] = sl * u[i];
-              du[i] = dh * sl;
-              dg[i] = dh * u[i] * (s * (1.0f + g[i] * (1.0f - s)));
-            }
-            *reinterpret_cast<uint2*>(A.c0 + o) = make_uint2(pack_bf16(dg[0], dg[1]), pack_bf16(dg[2], dg[3]));
-            *reinterpret_cast<uint2*>(A.c1 + o) = make_uint2(pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3]));
-            *reinterpret_cast<uint2*>(A.c2 + o) = make_uint2(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]));
+            *reinterpret_cast<float4*>(dst) = v;
           }
         }
       }
+    } else {
+      // 8 q per lane (16 bytes of bf16)
+      constexpr int LPR = W / 8;
+      constexpr int RPI = 64 / LPR;
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; it++) {
+        const int r = it * RPI + lane / LPR;
+        const int q = (lane % LPR) * 8;
+        const int p = wp + 32 * b + r;
+        if (p < p_valid && q_base + q < q_valid) {
+          const size_t o = (size_t)(p_row0 + p) * A.c_ld + q0_col + q_base + q;
+          const float4 x0 = *reinterpret_cast<const float4*>(wlds + r * PITCH + q * 4);
+          const float4 x1 = *reinterpret_cast<const float4*>(wlds + r * PITCH + q * 4 + 16);
+          const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+          if (EPI == EPI_BF16) {
+            *reinterpret_cast<uint4*>(A.c0 + o) =
+                make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+          } else if (EPI == EPI_SWIGLU) {  // x = G; the second staged tensor is U
+            const float4 y0 = *reinterpret_cast<const float4*>(wlds + 8192 + r * PITCH + q * 4);
+            const float4 y1 = *reinterpret_cast<const float4*>(wlds + 8192 + r * PITCH + q * 4 + 16);
+            const float u[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
+            float h[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) h[i] = x[i] / (1.0f + __expf(-x[i])) * u[i];
+            *reinterpret_cast<uint4*>(A.c0 + o) =
+                make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+            *reinterpret_cast<uint4*>(A.c1 + o) =
+                make_uint4(pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3]), pack_bf16(u[4], u[5]), pack_bf16(u[6], u[7]));
+            *reinterpret_cast<uint4*>(A.c2 + o) =
+                make_uint4(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]), pack_bf16(h[4], h[5]), pack_bf16(h[6], h[7]));
+          } else {  // EPI_DSWIGLU: x = dH; read saved G, U; write dG, dU, H
+            const uint4 gi = *reinterpret_cast<const uint4*>(A.g_in + o);
+            const uint4 ui = *reinterpret_cast<const uint4*>(A.u_in + o);
+            const float g[8] = {bf16lo(gi.x), bf16hi(gi.x), bf16lo(gi.y), bf16hi(gi.y), bf16lo(gi.z), bf16hi(gi.z), bf16lo(gi.w), bf16hi(gi.w)};
+            const float u[8] = {bf16lo(ui.x), bf16hi(ui.x), bf16lo(ui.y), bf16hi(ui.y), bf16lo(ui.z), bf16hi(ui.z), bf16lo(ui.w), bf16hi(ui.w)};
+            float dg[8], du[8], h[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+              const float sg = 1.0f / (1.0f + __expf(-g[i]));
+              const float sl = g[i] * sg;
+              h[i] = sl * u[i];
+              du[i] = x[i] * sl;
+              dg[i] = x[i] * u[i] * (sg * (1.0f + g[i] * (1.0f - sg)));
+            }
+            *reinterpret_cast<uint4*>(A.c0 + o) =
+                make_uint4(pack_bf16(dg[0], dg[1]), pack_bf16(dg[2], dg[3]), pack_bf16(dg[4], dg[5]), pack_bf16(dg[6], dg[7]));
+            *reinterpret_cast<uint4*>(A.c1 + o) =
+                make_uint4(pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3]), pack_bf16(du[4], du[5]), pack_bf16(du[6], du[7]));
+            *reinterpret_cast<uint4*>(A.c2 + o) =
+                make_uint4(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]), pack_bf16(h[4], h[5]), pack_bf16(h[6], h[7]));
+          }
+        }
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // the read-back is complete before the next 32 rows overwrite the buffer
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
