@@ -488,7 +488,7 @@ def unpermute_combine_scale(y_scale, row_of_slot, topk_w):
     return np.sqrt(((w[:, :, None] * q[ros]) ** 2).sum(axis=1))
 
 
-def layer_scales(x, topk_idx, topk_w, w_gate, w_up, w_down, dout, n_experts):
+def layer_scales_staged(x, topk_idx, topk_w, w_gate, w_up, w_down, dout, n_experts):
     """Scales of every output of one forward+backward of the layer (out, dx, dtopk_w, dw_gate, dw_up, dw_down),
     assembled from the stage scales along the staged evaluation."""
     Kp = np.asarray(topk_idx).shape[1]
@@ -508,6 +508,75 @@ def layer_scales(x, topk_idx, topk_w, w_gate, w_up, w_down, dout, n_experts):
     mX = np.sqrt(dX * dX + qX * qX)
     q_dx = np.sqrt((mX[rr] ** 2).sum(axis=1))
     return {"out": q_out, "dx": q_dx, "dtopk_w": q_dw, "dw_gate": qWg, "dw_up": qWu, "dw_down": qWd}
+
+
+def layer_scales(x, topk_idx, topk_w, w_gate, w_up, w_down, dout, n_experts, tokens=None, f_cols=None):
+    """The same scales by the per-token definition, with the slice mode of layer_backward: `tokens` restricts out,
+    dx and dtopk_w to those tokens, `f_cols` restricts the weight-gradient scales to those f-indices.  Pass an
+    empty list to skip either part."""
+    x = np.asarray(x)
+    idx = np.asarray(topk_idx).astype(np.int64)
+    w = np.asarray(topk_w, dtype=F64)
+    g = np.asarray(dout)
+    T, d = x.shape
+    Kp = idx.shape[1]
+    f = np.asarray(w_gate).shape[2]
+    res = {"out": None, "dx": None, "dtopk_w": None, "dw_gate": None, "dw_up": None, "dw_down": None}
+
+    toks = np.arange(T) if tokens is None else np.asarray(tokens, dtype=np.int64)
+    if toks.size:
+        q_out2 = np.zeros((toks.size, d), dtype=F64)
+        q_dx2 = np.zeros((toks.size, d), dtype=F64)
+        q_dw = np.zeros((toks.size, Kp), dtype=F64)
+        sub_idx = idx[toks]
+        for e in np.unique(sub_idx):
+            ti, ji = np.nonzero(sub_idx == e)
+            Wg = np.asarray(w_gate[e], dtype=F64)
+            Wu = np.asarray(w_up[e], dtype=F64)
+            Wd = np.asarray(w_down[e], dtype=F64)
+            X = np.asarray(x[toks[ti]], dtype=F64)
+            D = np.asarray(g[toks[ti]], dtype=F64)
+            wt = w[toks[ti], ji][:, None]
+            G, U, sG, sU, mH = _expert_magnitudes(X, Wg, Wu, Wd)
+            Y = (silu(G) * U) @ Wd
+            mY = np.sqrt(Y * Y + quad(mH, Wd) ** 2)
+            np.add.at(q_out2, ti, (wt * mY) ** 2)
+            q_dw[ti, ji] = np.sqrt(((D * mY) ** 2).sum(axis=1))
+            dY = wt * D
+            dH = dY @ Wd.T
+            mdH = np.sqrt(dH * dH + quad(dY, Wd.T) ** 2)
+            mdG = np.sqrt((mdH * U * silu_grad(G)) ** 2 + (dH * silu_grad(G) * sU) ** 2 + (dH * U * silu_grad2(G) * sG) ** 2)
+            mdU = np.sqrt((mdH * silu(G)) ** 2 + (dH * silu_grad(G) * sG) ** 2)
+            dG = dH * U * silu_grad(G)
+            dU = dH * silu(G)
+            dX = dG @ Wg.T + dU @ Wu.T
+            np.add.at(q_dx2, ti, dX * dX + quad(mdG, Wg.T) ** 2 + quad(mdU, Wu.T) ** 2)
+        res["out"], res["dx"], res["dtopk_w"] = np.sqrt(q_out2), np.sqrt(q_dx2), q_dw
+
+    cols = np.arange(f) if f_cols is None else np.asarray(f_cols, dtype=np.int64)
+    if cols.size:
+        qWg = np.zeros((n_experts, d, cols.size), dtype=F64)
+        qWu = np.zeros((n_experts, d, cols.size), dtype=F64)
+        qWd = np.zeros((n_experts, cols.size, d), dtype=F64)
+        for e in range(n_experts):
+            ti, ji = np.nonzero(idx == e)
+            if ti.size == 0:
+                continue
+            Wg = np.asarray(np.asarray(w_gate[e])[:, cols], dtype=F64)
+            Wu = np.asarray(np.asarray(w_up[e])[:, cols], dtype=F64)
+            Wd = np.asarray(np.asarray(w_down[e])[cols, :], dtype=F64)
+            X = np.asarray(x[ti], dtype=F64)
+            dY = w[ti, ji][:, None] * np.asarray(g[ti], dtype=F64)
+            G, U, sG, sU, mH = _expert_magnitudes(X, Wg, Wu, Wd)
+            dH = dY @ Wd.T
+            mdH = np.sqrt(dH * dH + quad(dY, Wd.T) ** 2)
+            mdG = np.sqrt((mdH * U * silu_grad(G)) ** 2 + (dH * silu_grad(G) * sU) ** 2 + (dH * U * silu_grad2(G) * sG) ** 2)
+            mdU = np.sqrt((mdH * silu(G)) ** 2 + (dH * silu_grad(G) * sG) ** 2)
+            qWg[e] = quad(X.T, mdG)
+            qWu[e] = quad(X.T, mdU)
+            qWd[e] = quad(mH.T, dY)
+        res["dw_gate"], res["dw_up"], res["dw_down"] = qWg, qWu, qWd
+    return res
 
 
 def rel_to_max_error(got, ref):

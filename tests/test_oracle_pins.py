@@ -418,6 +418,16 @@ def test_error_measures_and_scales():
     logits[:, 3] = -1e30
     idx, w, _ = O.route_topk(logits, 2, 0, True)
     sc = O.layer_scales(x, idx, w, Wg, Wu, Wd, dout, 5)
+    # per-token evaluation == staged evaluation; slices == full[slice]
+    st = O.layer_scales_staged(x, idx, w, Wg, Wu, Wd, dout, 5)
+    for key in sc:
+        np.testing.assert_allclose(sc[key], st[key], rtol=1e-11, atol=1e-14)
+    sl = O.layer_scales(x, idx, w, Wg, Wu, Wd, dout, 5, tokens=[6, 0], f_cols=[3, 1])
+    np.testing.assert_allclose(sl["out"], sc["out"][[6, 0]], rtol=1e-13)
+    np.testing.assert_allclose(sl["dx"], sc["dx"][[6, 0]], rtol=1e-13)
+    np.testing.assert_allclose(sl["dtopk_w"], sc["dtopk_w"][[6, 0]], rtol=1e-13)
+    np.testing.assert_allclose(sl["dw_gate"], sc["dw_gate"][:, :, [3, 1]], rtol=1e-13)
+    np.testing.assert_allclose(sl["dw_down"], sc["dw_down"][:, [3, 1], :], rtol=1e-13)
     g = O.layer_backward(x, idx, w, Wg, Wu, Wd, dout)
     out, _ = O.layer_forward(x, idx, w, Wg, Wu, Wd)
     assert sc["out"].shape == out.shape and sc["dx"].shape == g["dx"].shape
