@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-streaming", action="store_true", help="skip the permute/combine bandwidth measurement")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 512 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens of the workload the oracle is timed on (0 = auto)")
     return ap.parse_args()
 
@@ -112,7 +114,8 @@ def run_layer_bench(moe, W, args):
 
 def run_streaming_bench(moe, W, steps):
     """permute / combine family on the imbalance workload's shape (working set 671 MB per kernel, larger than the
-    256 MB last-level cache); two buffer sets are alternated so no launch re-reads what the previous one wrote."""
+    256 MB last-level cache).  Each kernel is timed in its own loop over three rotating buffer sets, so no launch
+    finds in cache what an earlier launch touched."""
     import numpy as np
     import torch
     wl = W.WORKLOADS["imbalance"]
@@ -122,10 +125,9 @@ def run_streaming_bench(moe, W, steps):
     d_logits = torch.from_numpy(logits).cuda()
     N, T, d, Kp, Et = s.N, s.T, s.d_model, s.K_slots, s.E_total
     sets = []
-    for i in range(2):
-        x = dev_bf16(W.make_tokens(sh, seed=i))
+    for i in range(3):
         sets.append(dict(
-            x=x, dout=dev_bf16(W.make_dout(sh, seed=i)),
+            x=dev_bf16(W.make_tokens(sh, seed=i)), dout=dev_bf16(W.make_dout(sh, seed=i)),
             x_perm=torch.empty((N, d), dtype=torch.bfloat16, device="cuda"),
             y_perm=torch.randn((N, d), device="cuda").to(torch.bfloat16),
             dy_perm=torch.empty((N, d), dtype=torch.bfloat16, device="cuda"),
@@ -140,46 +142,65 @@ def run_streaming_bench(moe, W, steps):
     sor = torch.empty((N,), dtype=torch.int32, device="cuda")
     ws = torch.empty(moe.workspace_bytes(s), dtype=torch.uint8, device="cuda")
     moe.moe_route_topk(s, d_logits, idx, w, None)
-
-    def one(i):
-        b = sets[i % 2]
-        moe.moe_permute(s, b["x"], idx, b["x_perm"], counts, offsets, ros, sor, ws)
-        moe.moe_unpermute_combine(s, b["y_perm"], ros, w, b["out"])
-        moe.moe_unpermute_combine_bwd(s, b["dout"], b["y_perm"], ros, w, b["dy_perm"], b["dtw"])
-        moe.moe_permute_bwd(s, b["y_perm"], ros, b["dx"])
-
-    for i in range(4):
-        one(i)
+    calls = {
+        "moe_permute": lambda b: moe.moe_permute(s, b["x"], idx, b["x_perm"], counts, offsets, ros, sor, ws),
+        "moe_unpermute_combine": lambda b: moe.moe_unpermute_combine(s, b["y_perm"], ros, w, b["out"]),
+        "moe_unpermute_combine_bwd": lambda b: moe.moe_unpermute_combine_bwd(s, b["dout"], b["y_perm"], ros, w, b["dy_perm"], b["dtw"]),
+        "moe_permute_bwd": lambda b: moe.moe_permute_bwd(s, b["y_perm"], ros, b["dx"]),
+    }
+    calls["moe_permute"](sets[0])      # the maps the other calls use
     torch.cuda.synchronize()
-    moe.profile_reset()
-    moe.profile_enable(True)
-    for i in range(steps):
-        one(i)
-    torch.cuda.synchronize()
-    moe.profile_enable(False)
-    recs = moe.profile_records()
-    moe.profile_reset()
-    per = {}
-    for name, ms in recs:
-        per.setdefault(name, []).append(ms)
     out = {"workload": "imbalance: T=16384 d=4096 E=128 top-4 (N=65536)", "peak_GBs": PEAK_HBM_GBS, "kernels": {}}
-    for name, v in per.items():
-        avg = sum(v) / len(v)
-        b = stream_bytes_per_launch(name, sh)
-        ent = {"avg_us": round(avg * 1e3, 2)}
-        if b:
-            ent["algorithmic_MB"] = round(b / 1e6, 1)
-            ent["GBs"] = round(b / (avg * 1e-3) / 1e9, 1)
-            ent["frac_hbm_peak"] = round(b / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
-        out["kernels"][name] = ent
-    pk = [k for k in ("perm_rank", "perm_scan", "perm_scatter_gather") if k in per]
-    tot = sum(sum(per[k]) / len(per[k]) for k in pk)
-    b = stream_bytes_per_launch("perm_scatter_gather", sh)
-    out["moe_permute_total"] = {"avg_us": round(tot * 1e3, 2), "GBs": round(b / (tot * 1e-3) / 1e9, 1),
-                                "frac_hbm_peak": round(b / (tot * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    for call, fn in calls.items():
+        for i in range(3):
+            fn(sets[i])
+        torch.cuda.synchronize()
+        moe.profile_reset()
+        moe.profile_enable(True)
+        for i in range(steps):
+            fn(sets[i % 3])
+        torch.cuda.synchronize()
+        moe.profile_enable(False)
+        per = {}
+        for name, ms in moe.profile_records():
+            per.setdefault(name, []).append(ms)
+        moe.profile_reset()
+        for name, v in per.items():
+            avg = sum(v) / len(v)
+            b = stream_bytes_per_launch(name, sh)
+            ent = {"avg_us": round(avg * 1e3, 2)}
+            if b:
+                ent["algorithmic_MB"] = round(b / 1e6, 1)
+                ent["GBs"] = round(b / (avg * 1e-3) / 1e9, 1)
+                ent["frac_hbm_peak"] = round(b / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+            out["kernels"][name] = ent
+        if call == "moe_permute":
+            tot = sum(sum(v) / len(v) for v in per.values())
+            b = stream_bytes_per_launch("perm_scatter_gather", sh)
+            out["moe_permute_total"] = {"avg_us": round(tot * 1e3, 2), "GBs": round(b / (tot * 1e-3) / 1e9, 1),
+                                        "frac_hbm_peak": round(b / (tot * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
     del sets
     torch.cuda.empty_cache()
     return out
+
+
+def run_copy_calibration():
+    """A plain device-to-device copy of known size (512 MiB read + 512 MiB written per launch, 5 launches): the yard
+    stick the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by."""
+    import torch
+    n = 512 * 1024 * 1024
+    a = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+    b = torch.empty_like(a)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 5
+    return {"bytes_read": n, "bytes_written": n, "launches": 5, "avg_us": round(ms * 1e3, 1),
+            "GBs_read_plus_write": round(2 * n / (ms * 1e-3) / 1e9, 1)}
 
 
 def run_cpu_baseline(W, inp, sh, sample_tokens):
@@ -267,6 +288,8 @@ def main():
     }
     if not args.no_streaming:
         res["permute_combine"] = run_streaming_bench(moe, W, steps=20)
+    if args.copy_calibration:
+        res["copy_calibration"] = run_copy_calibration()
     if not args.no_cpu_baseline:
         n = args.cpu_sample_tokens
         if n <= 0:

@@ -74,31 +74,50 @@ __global__ __launch_bounds__(256) void perm_rank_kernel(const int32_t* __restric
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ block_hist, int32_t* __restrict__ counts,
                                                          int32_t* __restrict__ offsets, int nblk, int Et) {
+  // Thread (g, e): expert e, blocks [g*chunk, (g+1)*chunk).  G = 1024 / E' groups share the walk over the blocks.
+  __shared__ int32_t part[kMaxExperts];   // [G][Et] chunk totals, then exclusive prefixes over g
   __shared__ int32_t tot[kMaxExperts];
   __shared__ int32_t scan[kMaxExperts];
-  const int e = threadIdx.x;
-  int total = 0;
-  if (e < Et) {
-    for (int b = 0; b < nblk; b++) total += block_hist[(size_t)b * Et + e];
+  const int tid = threadIdx.x;
+  const int G = kMaxExperts / Et;
+  const int g = tid / Et, e = tid % Et;
+  const int chunk = (nblk + G - 1) / G;
+  const int b0 = g * chunk, b1 = min(nblk, b0 + chunk);
+  const bool active = g < G;
+  int sum = 0;
+  if (active)
+    for (int b = b0; b < b1; b++) sum += block_hist[(size_t)b * Et + e];
+  if (active) part[g * Et + e] = sum;
+  __syncthreads();
+  if (tid < Et) {
+    int run = 0;
+    for (int gg = 0; gg < G; gg++) {
+      const int c = part[gg * Et + tid];
+      part[gg * Et + tid] = run;
+      run += c;
+    }
+    tot[tid] = run;
+  } else {
+    tot[tid] = 0;
   }
-  tot[e] = (e < Et) ? total : 0;
-  scan[e] = tot[e];
+  scan[tid] = (tid < Et) ? tot[tid] : 0;
   __syncthreads();
   // Hillis-Steele inclusive scan over the (at most 1024) experts
   for (int o = 1; o < kMaxExperts; o <<= 1) {
-    int v = (e >= o) ? scan[e - o] : 0;
+    int v = (tid >= o) ? scan[tid - o] : 0;
     __syncthreads();
-    scan[e] += v;
+    scan[tid] += v;
     __syncthreads();
   }
-  if (e < Et) {
-    const int off = scan[e] - tot[e];
-    counts[e] = tot[e];
-    offsets[e] = off;
-    if (e == Et - 1) offsets[Et] = scan[e];
-    int run = off;
-    for (int b = 0; b < nblk; b++) {
-      int c = block_hist[(size_t)b * Et + e];
+  if (tid < Et) {
+    counts[tid] = tot[tid];
+    offsets[tid] = scan[tid] - tot[tid];
+    if (tid == Et - 1) offsets[Et] = scan[tid];
+  }
+  if (active) {
+    int run = scan[e] - tot[e] + part[g * Et + e];
+    for (int b = b0; b < b1; b++) {
+      const int c = block_hist[(size_t)b * Et + e];
       block_hist[(size_t)b * Et + e] = run;
       run += c;
     }
@@ -106,27 +125,84 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ b
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// 3. scatter the maps and gather the rows: one wavefront per token
+// The streaming kernels below give one wavefront one token.  KP is the number of slots per token K' when it is
+// small (1..8: the slot loop is unrolled, all K' row indices are fetched up front and the K' row accesses of a
+// vector are in flight together); KP = 0 is the general loop for any K'.  Rows move as 16-byte vectors per lane,
+// CHUNK vectors per lane at a time, with non-temporal hints (each byte is touched once).
 // ---------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void perm_scatter_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ topk_idx,
+constexpr int CHUNK = 4;  // 16-byte vectors per lane held in registers at once (4 x 64 x 16 B = 4 KB of a row)
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// Cache policy per kernel, chosen by measurement on the imbalance shape (671 MB per launch, cold caches): the
+// gather is indifferent and the combine backward runs fastest with ordinary accesses; the combine (many gathered
+// reads, one write) gains 7 % from non-temporal ones.
+constexpr bool kGatherNT = false, kCombineNT = true, kCombineBwdNT = false;
+template <bool NT> __device__ __forceinline__ u32x4 ld_row(const u32x4* p) { return NT ? __builtin_nontemporal_load(p) : *p; }
+template <bool NT> __device__ __forceinline__ void st_row(u32x4* p, u32x4 v) {
+  if (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// 3. scatter the maps and gather the rows
+// ---------------------------------------------------------------------------------------------------------
+template <int KP>
+__global__ __launch_bounds__(256) void perm_scatter_kernel(const u32x4* __restrict__ x, const int32_t* __restrict__ topk_idx,
                                                            const int32_t* __restrict__ lrank, const int32_t* __restrict__ block_base,
-                                                           uint4* __restrict__ x_perm, int32_t* __restrict__ row_of_slot,
+                                                           u32x4* __restrict__ x_perm, int32_t* __restrict__ row_of_slot,
                                                            int32_t* __restrict__ slot_of_row, int T, int Kp, int Et, int dvec) {
   const int lane = threadIdx.x % kWave;
   const int t = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + threadIdx.x / kWave);
   if (t >= T) return;
-  const uint4* src = x ? x + (size_t)t * dvec : nullptr;
-  for (int j = 0; j < Kp; j++) {
-    const int s = t * Kp + j;
-    const int e = clamp_expert(topk_idx[s], Et);
-    const int row = block_base[(size_t)(s / kPermSlotsPerBlock) * Et + e] + lrank[s];
-    if (lane == 0) {
-      row_of_slot[s] = row;
-      slot_of_row[row] = s;
+  const u32x4* src = x ? x + (size_t)t * dvec : nullptr;
+  if (KP > 0) {
+    int rows[KP > 0 ? KP : 1];
+#pragma unroll
+    for (int j = 0; j < KP; j++) {
+      const int s = t * KP + j;
+      const int e = clamp_expert(topk_idx[s], Et);
+      rows[j] = block_base[(size_t)(s / kPermSlotsPerBlock) * Et + e] + lrank[s];
+    }
+    if (lane < KP) {
+      int row = rows[0];
+#pragma unroll
+      for (int j = 1; j < KP; j++) row = (lane == j) ? rows[j] : row;
+      row_of_slot[t * KP + lane] = row;
+      slot_of_row[row] = t * KP + lane;
     }
     if (src) {
-      uint4* dst = x_perm + (size_t)row * dvec;
-      for (int v = lane; v < dvec; v += kWave) dst[v] = src[v];
+      for (int v0 = 0; v0 < dvec; v0 += CHUNK * kWave) {
+        u32x4 r[CHUNK];
+#pragma unroll
+        for (int i = 0; i < CHUNK; i++) {
+          const int v = v0 + i * kWave + lane;
+          if (v < dvec) r[i] = ld_row<kGatherNT>(src + v);
+        }
+#pragma unroll
+        for (int j = 0; j < KP; j++) {
+          u32x4* dst = x_perm + (size_t)rows[j] * dvec;
+#pragma unroll
+          for (int i = 0; i < CHUNK; i++) {
+            const int v = v0 + i * kWave + lane;
+            if (v < dvec) st_row<kGatherNT>(dst + v, r[i]);
+          }
+        }
+      }
+    }
+  } else {
+    for (int j = 0; j < Kp; j++) {
+      const int s = t * Kp + j;
+      const int e = clamp_expert(topk_idx[s], Et);
+      const int row = block_base[(size_t)(s / kPermSlotsPerBlock) * Et + e] + lrank[s];
+      if (lane == 0) {
+        row_of_slot[s] = row;
+        slot_of_row[row] = s;
+      }
+      if (src) {
+        u32x4* dst = x_perm + (size_t)row * dvec;
+        for (int v = lane; v < dvec; v += kWave) st_row<kGatherNT>(dst + v, src[v]);
+      }
     }
   }
 }
@@ -134,67 +210,146 @@ __global__ __launch_bounds__(256) void perm_scatter_kernel(const uint4* __restri
 // ---------------------------------------------------------------------------------------------------------
 // combine: out[t] = sum_j w[t,j] * y[row_of_slot[t*K'+j]]   (UNIT = true: all weights 1 -> permute_bwd)
 // ---------------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void fma_bf16x8(float (&acc)[8], const uint4& v, float w) {
+__device__ __forceinline__ void fma_bf16x8(float (&acc)[8], const u32x4& v, float w) {
   acc[0] += w * bf16lo(v.x); acc[1] += w * bf16hi(v.x);
   acc[2] += w * bf16lo(v.y); acc[3] += w * bf16hi(v.y);
   acc[4] += w * bf16lo(v.z); acc[5] += w * bf16hi(v.z);
   acc[6] += w * bf16lo(v.w); acc[7] += w * bf16hi(v.w);
 }
+__device__ __forceinline__ u32x4 pack8(const float (&a)[8]) {
+  u32x4 o;
+  o.x = pack_bf16(a[0], a[1]); o.y = pack_bf16(a[2], a[3]); o.z = pack_bf16(a[4], a[5]); o.w = pack_bf16(a[6], a[7]);
+  return o;
+}
 
-template <bool UNIT>
-__global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ y, const int32_t* __restrict__ row_of_slot,
-                                                      const float* __restrict__ topk_w, uint4* __restrict__ out, int T, int Kp,
+template <int KP, bool UNIT>
+__global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ y, const int32_t* __restrict__ row_of_slot,
+                                                      const float* __restrict__ topk_w, u32x4* __restrict__ out, int T, int Kp,
                                                       int dvec) {
   const int lane = threadIdx.x % kWave;
   const int t = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + threadIdx.x / kWave);
   if (t >= T) return;
-  const int32_t* rows = row_of_slot + (size_t)t * Kp;
-  const float* w = UNIT ? nullptr : topk_w + (size_t)t * Kp;
-  for (int v = lane; v < dvec; v += kWave) {
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int j = 0; j < Kp; j++) {
-      const uint4 val = y[(size_t)rows[j] * dvec + v];
-      fma_bf16x8(acc, val, UNIT ? 1.0f : w[j]);
+  u32x4* dst = out + (size_t)t * dvec;
+  if (KP > 0) {
+    const u32x4* rowp[KP > 0 ? KP : 1];
+    float w[KP > 0 ? KP : 1];
+#pragma unroll
+    for (int j = 0; j < KP; j++) {
+      rowp[j] = y + (size_t)row_of_slot[(size_t)t * KP + j] * dvec;
+      w[j] = UNIT ? 1.0f : topk_w[(size_t)t * KP + j];
     }
-    uint4 o;
-    o.x = pack_bf16(acc[0], acc[1]); o.y = pack_bf16(acc[2], acc[3]);
-    o.z = pack_bf16(acc[4], acc[5]); o.w = pack_bf16(acc[6], acc[7]);
-    out[(size_t)t * dvec + v] = o;
+    constexpr int VU = (KP <= 4) ? 2 : 1;  // vectors per lane per iteration: keep KP*VU row loads in flight
+    for (int v0 = 0; v0 < dvec; v0 += VU * kWave) {
+      u32x4 val[VU][KP > 0 ? KP : 1];
+#pragma unroll
+      for (int i = 0; i < VU; i++) {
+        const int v = v0 + i * kWave + lane;
+        if (v < dvec) {
+#pragma unroll
+          for (int j = 0; j < KP; j++) val[i][j] = ld_row<kCombineNT>(rowp[j] + v);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < VU; i++) {
+        const int v = v0 + i * kWave + lane;
+        if (v < dvec) {
+          float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int j = 0; j < KP; j++) fma_bf16x8(acc, val[i][j], w[j]);  // slot order, fp32
+          st_row<kCombineNT>(dst + v, pack8(acc));
+        }
+      }
+    }
+  } else {
+    const int32_t* rows = row_of_slot + (size_t)t * Kp;
+    const float* w = UNIT ? nullptr : topk_w + (size_t)t * Kp;
+    for (int v = lane; v < dvec; v += kWave) {
+      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < Kp; j++) fma_bf16x8(acc, y[(size_t)rows[j] * dvec + v], UNIT ? 1.0f : w[j]);
+      st_row<kCombineNT>(dst + v, pack8(acc));
+    }
   }
 }
 
 // combine_bwd: dy[row] = bf16(w * dout[t]);  dw[t,j] = <dout[t], y[row]>
-__global__ __launch_bounds__(256) void combine_bwd_kernel(const uint4* __restrict__ dout, const uint4* __restrict__ y,
+template <int KP>
+__global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restrict__ dout, const u32x4* __restrict__ y,
                                                           const int32_t* __restrict__ row_of_slot, const float* __restrict__ topk_w,
-                                                          uint4* __restrict__ dy, float* __restrict__ dtopk_w, int T, int Kp, int dvec) {
+                                                          u32x4* __restrict__ dy, float* __restrict__ dtopk_w, int T, int Kp, int dvec) {
   const int lane = threadIdx.x % kWave;
   const int t = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + threadIdx.x / kWave);
   if (t >= T) return;
-  const uint4* g = dout + (size_t)t * dvec;
-  for (int j = 0; j < Kp; j++) {
-    const int s = t * Kp + j;
-    const int row = row_of_slot[s];
-    const float w = topk_w[s];
-    const uint4* yr = y + (size_t)row * dvec;
-    uint4* dyr = dy + (size_t)row * dvec;
-    float dot = 0.f;
-    for (int v = lane; v < dvec; v += kWave) {
-      const uint4 gv = g[v];
-      const uint4 yv = yr[v];
-      float a[8] = {bf16lo(gv.x), bf16hi(gv.x), bf16lo(gv.y), bf16hi(gv.y), bf16lo(gv.z), bf16hi(gv.z), bf16lo(gv.w), bf16hi(gv.w)};
-      float b[8] = {bf16lo(yv.x), bf16hi(yv.x), bf16lo(yv.y), bf16hi(yv.y), bf16lo(yv.z), bf16hi(yv.z), bf16lo(yv.w), bf16hi(yv.w)};
-      uint4 o;
-      o.x = pack_bf16(w * a[0], w * a[1]); o.y = pack_bf16(w * a[2], w * a[3]);
-      o.z = pack_bf16(w * a[4], w * a[5]); o.w = pack_bf16(w * a[6], w * a[7]);
-      dyr[v] = o;
+  const u32x4* g = dout + (size_t)t * dvec;
+  if (KP > 0) {
+    size_t rowoff[KP > 0 ? KP : 1];
+    float w[KP > 0 ? KP : 1], dot[KP > 0 ? KP : 1];
 #pragma unroll
-      for (int q = 0; q < 8; q++) dot += a[q] * b[q];
+    for (int j = 0; j < KP; j++) {
+      rowoff[j] = (size_t)row_of_slot[(size_t)t * KP + j] * dvec;
+      w[j] = topk_w[(size_t)t * KP + j];
+      dot[j] = 0.f;
+    }
+    for (int v = lane; v < dvec; v += kWave) {
+      const u32x4 gv = ld_row<kCombineBwdNT>(g + v);
+      u32x4 yv[KP > 0 ? KP : 1];
+#pragma unroll
+      for (int j = 0; j < KP; j++) yv[j] = ld_row<kCombineBwdNT>(y + rowoff[j] + v);
+      const float a[8] = {bf16lo(gv.x), bf16hi(gv.x), bf16lo(gv.y), bf16hi(gv.y), bf16lo(gv.z), bf16hi(gv.z), bf16lo(gv.w), bf16hi(gv.w)};
+#pragma unroll
+      for (int j = 0; j < KP; j++) {
+        float sc[8];
+#pragma unroll
+        for (int q = 0; q < 8; q++) sc[q] = w[j] * a[q];
+        st_row<kCombineBwdNT>(dy + rowoff[j] + v, pack8(sc));
+        const u32x4 yy = yv[j];
+        const float b[8] = {bf16lo(yy.x), bf16hi(yy.x), bf16lo(yy.y), bf16hi(yy.y), bf16lo(yy.z), bf16hi(yy.z), bf16lo(yy.w), bf16hi(yy.w)};
+#pragma unroll
+        for (int q = 0; q < 8; q++) dot[j] += a[q] * b[q];
+      }
     }
 #pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
-    if (lane == 0) dtopk_w[s] = dot;
+    for (int j = 0; j < KP; j++) {
+      float dsum = dot[j];
+#pragma unroll
+      for (int o = kWave / 2; o > 0; o >>= 1) dsum += __shfl_xor(dsum, o, kWave);
+      if (lane == 0) dtopk_w[(size_t)t * KP + j] = dsum;
+    }
+  } else {
+    for (int j = 0; j < Kp; j++) {
+      const int s = t * Kp + j;
+      const size_t ro = (size_t)row_of_slot[s] * dvec;
+      const float w = topk_w[s];
+      float dot = 0.f;
+      for (int v = lane; v < dvec; v += kWave) {
+        const u32x4 gv = g[v];
+        const u32x4 yy = y[ro + v];
+        const float a[8] = {bf16lo(gv.x), bf16hi(gv.x), bf16lo(gv.y), bf16hi(gv.y), bf16lo(gv.z), bf16hi(gv.z), bf16lo(gv.w), bf16hi(gv.w)};
+        const float b[8] = {bf16lo(yy.x), bf16hi(yy.x), bf16lo(yy.y), bf16hi(yy.y), bf16lo(yy.z), bf16hi(yy.z), bf16lo(yy.w), bf16hi(yy.w)};
+        float sc[8];
+#pragma unroll
+        for (int q = 0; q < 8; q++) { sc[q] = w * a[q]; dot += a[q] * b[q]; }
+        st_row<kCombineBwdNT>(dy + ro + v, pack8(sc));
+      }
+#pragma unroll
+      for (int o = kWave / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
+      if (lane == 0) dtopk_w[s] = dot;
+    }
   }
 }
+
+// Picks the unrolled instantiation for K' = 1..8 and the general one otherwise.
+#define MOE_DISPATCH_KP(Kp_, CALL)                                                     \
+  switch (Kp_) {                                                                       \
+    case 1: { constexpr int KP = 1; CALL; } break;                                     \
+    case 2: { constexpr int KP = 2; CALL; } break;                                     \
+    case 3: { constexpr int KP = 3; CALL; } break;                                     \
+    case 4: { constexpr int KP = 4; CALL; } break;                                     \
+    case 5: { constexpr int KP = 5; CALL; } break;                                     \
+    case 6: { constexpr int KP = 6; CALL; } break;                                     \
+    case 7: { constexpr int KP = 7; CALL; } break;                                     \
+    case 8: { constexpr int KP = 8; CALL; } break;                                     \
+    default: { constexpr int KP = 0; CALL; } break;                                    \
+  }
 
 }  // namespace moe
 
@@ -226,8 +381,9 @@ extern "C" int moe_permute(const moe_shape* shape, const uint16_t* x, const int3
   // with no slots the scan still defines counts = 0 and offsets = 0
   MOE_LAUNCH("perm_scan", st, perm_scan_kernel, dim3(1), dim3(1024), 0, st, block_hist, counts, offsets, nblk, D.Et);
   if (D.T > 0) {
-    MOE_LAUNCH("perm_scatter_gather", st, perm_scatter_kernel, dim3((D.T + 3) / 4), dim3(256), 0, st, reinterpret_cast<const uint4*>(x), topk_idx,
-                       lrank, block_hist, reinterpret_cast<uint4*>(x_perm), row_of_slot, slot_of_row, D.T, D.Kp, D.Et, D.d / 8);
+    MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("perm_scatter_gather", st, (perm_scatter_kernel<KP>), dim3((D.T + 3) / 4), dim3(256), 0, st,
+                                     reinterpret_cast<const u32x4*>(x), topk_idx, lrank, block_hist, reinterpret_cast<u32x4*>(x_perm),
+                                     row_of_slot, slot_of_row, D.T, D.Kp, D.Et, D.d / 8));
   }
   return launch_status();
 }
@@ -241,9 +397,10 @@ extern "C" int moe_permute_bwd(const moe_shape* shape, const uint16_t* dx_perm, 
   MOE_REQUIRE_PTR(dx_perm); MOE_REQUIRE_PTR(row_of_slot); MOE_REQUIRE_PTR(dx);
   MOE_REQUIRE_ALIGNED(dx_perm); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(dx);
   if (D.T == 0) return MOE_OK;
-  MOE_LAUNCH("permute_bwd", (hipStream_t)stream, (combine_kernel<true>), dim3((D.T + 3) / 4), dim3(256), 0, (hipStream_t)stream,
-                     reinterpret_cast<const uint4*>(dx_perm), row_of_slot, (const float*)nullptr, reinterpret_cast<uint4*>(dx),
-                     D.T, D.Kp, D.d / 8);
+  hipStream_t st = (hipStream_t)stream;
+  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("permute_bwd", st, (combine_kernel<KP, true>), dim3((D.T + 3) / 4), dim3(256), 0, st,
+                                   reinterpret_cast<const u32x4*>(dx_perm), row_of_slot, (const float*)nullptr,
+                                   reinterpret_cast<u32x4*>(dx), D.T, D.Kp, D.d / 8));
   return launch_status();
 }
 
@@ -256,9 +413,10 @@ extern "C" int moe_unpermute_combine(const moe_shape* shape, const uint16_t* y_p
   MOE_REQUIRE_PTR(y_perm); MOE_REQUIRE_PTR(row_of_slot); MOE_REQUIRE_PTR(topk_w); MOE_REQUIRE_PTR(out);
   MOE_REQUIRE_ALIGNED(y_perm); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(topk_w); MOE_REQUIRE_ALIGNED(out);
   if (D.T == 0) return MOE_OK;
-  MOE_LAUNCH("unpermute_combine", (hipStream_t)stream, (combine_kernel<false>), dim3((D.T + 3) / 4), dim3(256), 0, (hipStream_t)stream,
-                     reinterpret_cast<const uint4*>(y_perm), row_of_slot, topk_w, reinterpret_cast<uint4*>(out), D.T, D.Kp,
-                     D.d / 8);
+  hipStream_t st = (hipStream_t)stream;
+  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("unpermute_combine", st, (combine_kernel<KP, false>), dim3((D.T + 3) / 4), dim3(256), 0, st,
+                                   reinterpret_cast<const u32x4*>(y_perm), row_of_slot, topk_w, reinterpret_cast<u32x4*>(out),
+                                   D.T, D.Kp, D.d / 8));
   return launch_status();
 }
 
@@ -274,8 +432,9 @@ extern "C" int moe_unpermute_combine_bwd(const moe_shape* shape, const uint16_t*
   MOE_REQUIRE_ALIGNED(dout); MOE_REQUIRE_ALIGNED(y_perm); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(topk_w);
   MOE_REQUIRE_ALIGNED(dy_perm); MOE_REQUIRE_ALIGNED(dtopk_w);
   if (D.T == 0) return MOE_OK;
-  MOE_LAUNCH("unpermute_combine_bwd", (hipStream_t)stream, combine_bwd_kernel, dim3((D.T + 3) / 4), dim3(256), 0, (hipStream_t)stream,
-                     reinterpret_cast<const uint4*>(dout), reinterpret_cast<const uint4*>(y_perm), row_of_slot, topk_w,
-                     reinterpret_cast<uint4*>(dy_perm), dtopk_w, D.T, D.Kp, D.d / 8);
+  hipStream_t st = (hipStream_t)stream;
+  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("unpermute_combine_bwd", st, (combine_bwd_kernel<KP>), dim3((D.T + 3) / 4), dim3(256), 0, st,
+                                   reinterpret_cast<const u32x4*>(dout), reinterpret_cast<const u32x4*>(y_perm), row_of_slot,
+                                   topk_w, reinterpret_cast<u32x4*>(dy_perm), dtopk_w, D.T, D.Kp, D.d / 8));
   return launch_status();
 }
