@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E, published
 
+# HBM-side bytes per launch (read + written) of the grouped GEMM kernels on the mixtral workload, from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/grouped_gemm_mixtral_hbm_traffic.txt (scaled by the plain-copy
+# calibration of the same runs).  Counters cannot be read from inside this script; other workloads report null.
+MEASURED_TRAFFIC_BYTES = {"mixtral": {"ffn_fwd_gate_up_swiglu": 3969953486, "ffn_fwd_down": 2066579208, "ffn_bwd_dh_dswiglu": 3209306354, "ffn_bwd_dx": 4069909684, "ffn_bwd_dw_down": 3290660155, "ffn_bwd_dw_gate_up": 7049455602}}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -258,7 +263,8 @@ def main():
     if dom_flops:
         ach = dom_flops / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None, "kernel": dom,
+                    "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dom), "kernel": dom,
                     "avg_ms": round(kernels[dom]["avg_ms"], 4), "flops_per_launch": dom_flops}
     else:
         b = stream_bytes_per_launch(dom, sh) or 0

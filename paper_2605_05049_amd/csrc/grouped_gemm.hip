@@ -196,7 +196,11 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     q0_col = qt * TQ;
     k_len = A.k_dim;
   } else {
-    const long long per_e = (long long)A.n_p_tiles * A.n_q_tiles;
+    // Tiles of an expert are walked in 8 x 4 super-tiles (8 along p, 4 along q = the 32 tiles one XCD runs at a
+    // time): each p panel then meets 4 q panels and each q panel 8 p panels in that XCD's L2 instead of one
+    // panel being re-fetched for every tile of the other dimension.  The grid is padded to whole super-tiles.
+    const int sp = (A.n_p_tiles + 7) / 8, sq = (A.n_q_tiles + 3) / 4;
+    const long long per_e = (long long)sp * sq * 32;
     const long long total = per_e * A.Et;
     const long long chunk = (total + kNumXcd - 1) / kNumXcd;
     const long long within = blockIdx.x / kNumXcd;
@@ -204,8 +208,10 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     if (within >= chunk || lid >= total) return;
     expert = (int)(lid / per_e);
     const int local = (int)(lid % per_e);
-    const int qt = local / A.n_p_tiles;
-    const int pt = local % A.n_p_tiles;
+    const int super = local >> 5, in_super = local & 31;
+    const int pt = (super % sp) * 8 + (in_super & 7);
+    const int qt = (super / sp) * 4 + (in_super >> 3);
+    if (pt >= A.n_p_tiles || qt >= A.n_q_tiles) return;  // padding of the super-tile grid
     const int e_lo = A.offsets[expert], e_hi = A.offsets[expert + 1];
     k_len = e_hi - e_lo;
     krow0 = (size_t)e_lo;
@@ -541,12 +547,12 @@ extern "C" int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_pe
   A.p0 = h; A.p1 = nullptr; A.p_ld = D.f;
   A.q0 = dy_perm; A.q1 = nullptr; A.q_ld = D.d;
   A.f0 = dw_down; A.f1 = nullptr; A.f_expert_stride = (size_t)D.f * D.d; A.c_ld = D.d;
-  MOE_TRY((launch_gemm<1, true, true, 1, 1, EPI_F32>("ffn_bwd_dw_down", A, (long long)D.Et * A.n_p_tiles * A.n_q_tiles, st)));
+  MOE_TRY((launch_gemm<1, true, true, 1, 1, EPI_F32>("ffn_bwd_dw_down", A, (long long)D.Et * ((A.n_p_tiles + 7) / 8) * ((A.n_q_tiles + 3) / 4) * 32, st)));
   // dWg[e], dWu[e] = X_e^T dG_e, X_e^T dU_e   (rows d, columns f)
   A.p_dim = D.d; A.n_p_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.f; A.n_q_tiles = (D.f + 127) / 128;
   A.p0 = x_perm; A.p_ld = D.d;
   A.q0 = dg; A.q1 = du; A.q_ld = D.f;
   A.f0 = dw_gate; A.f1 = dw_up; A.f_expert_stride = (size_t)D.d * D.f; A.c_ld = D.f;
-  MOE_TRY((launch_gemm<1, true, true, 2, 1, EPI_F32>("ffn_bwd_dw_gate_up", A, (long long)D.Et * A.n_p_tiles * A.n_q_tiles, st)));
+  MOE_TRY((launch_gemm<1, true, true, 2, 1, EPI_F32>("ffn_bwd_dw_gate_up", A, (long long)D.Et * ((A.n_p_tiles + 7) / 8) * ((A.n_q_tiles + 3) / 4) * 32, st)));
   return launch_status();
 }
