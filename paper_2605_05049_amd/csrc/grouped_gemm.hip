@@ -20,12 +20,17 @@
 // Tiling: 512 threads = 8 wavefronts (2 along p x 4 along q); each wavefront owns 128 p x 64 q as 4x2 MFMA
 // 32x32x16 blocks (128 fp32 accumulators per lane).  Tiles stream HBM/L2 -> LDS with the direct 16-byte
 // global->LDS load (no register staging) into two 64 KB stages; step k+1 is in flight while step k is
-// multiplied, one barrier per step.  The LDS destination of a direct load is fixed by the lane id, so bank
+// multiplied, one barrier per step.  A direct load is addressed by a scalar base (advanced once per step) plus one
+// 32-bit per-lane offset that never changes, so the K loop does no per-lane address arithmetic.  The two wavefronts
+// that share a SIMD request their parts of the next stage at different times of a step (one right after the
+// barrier, the other half-way through its MFMAs): a wavefront is held up while its loads are accepted, and this way
+// its partner has MFMAs to issue meanwhile.  The LDS destination of a direct load is fixed by the lane id, so bank
 // conflicts are avoided by choosing WHICH 16-byte chunk each lane fetches (an XOR swizzle of the chunk index with
-// row bits), and the fragment reads apply the same swizzle.  Rows past the end of a ragged K (weight gradients)
-// are fetched from a zeroed page.  Row tiles of the ragged dimension come from a device-built schedule (no host
-// sync on the counts); the block-id -> tile map hands each XCD a contiguous run of tiles so that tiles sharing a
-// weight panel meet in one L2.
+// row bits), and the fragment reads apply the same swizzle.  Every request is a whole 128-byte line (KC) or four of
+// them (RC): the vector L1 handles about one line per two cycles whatever part of it is used.  Rows past the end of
+// a ragged K (weight gradients) are fetched from a zeroed page.  Row tiles of the ragged dimension come from a
+// device-built schedule (no host sync on the counts); the block-id -> tile map hands each XCD a contiguous run of
+// tiles so that tiles sharing a weight panel meet in one L2.
 #include "common.h"
 
 namespace moe {
@@ -41,6 +46,9 @@ constexpr int OPERAND_BYTES = TILE * BK * 2;    // 32 KB per operand per stage
 constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;  // P + Q
                                                 // two stages = 128 KB of the 160 KB of LDS
 constexpr int kNumXcd = 8;
+#ifndef MOE_EARLY_ISSUE_AT
+#define MOE_EARLY_ISSUE_AT 32   // k offset inside a step at which wavefronts 0..3 request their share of the next stage
+#endif
 
 enum Epilogue { EPI_BF16 = 0, EPI_SWIGLU = 1, EPI_DSWIGLU = 2, EPI_F32 = 3 };
 
@@ -70,41 +78,38 @@ struct GemmArgs {
 
 // One 256-wide operand of a tile, possibly made of two 128-wide halves from two tensors.
 struct TileOperand {
-  const uint16_t* base0;    // element (r = 0, k = 0) of the first half (or of the whole operand)
-  ptrdiff_t half_delta;     // elements from the first half's origin to the second half's (0 when not split)
+  const uint16_t* base0;    // element (r = 0, k = 0) of the operand (of its first half when split)
+  const uint16_t* base1;    // element (r = 0, k = 0) of the second half when split (else unused)
   size_t ld;                // elements between consecutive r (KC) or consecutive k (RC)
   int r_valid;              // valid r per half (<= 128 when split, <= 256 otherwise); beyond: clamped, never stored
 };
 
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// Per-thread source pointers of the 4 direct loads (16 bytes each) that fill this thread's share of one 32 KB
-// operand tile.  Wave w, instruction i fills LDS bytes [(4w+i)*1024, +1024); lane L fills 16 bytes at +16L.
-//   KC: LDS row r (128 bytes) = 8 chunks of 8 k-values; chunk c sits at position c ^ ((r >> 1) & 7).
-//   RC: LDS k-row (512 bytes) = 32 chunks of 8 r-values; chunk c sits at position c ^ ((k & 3) << 2).
+// A 32 KB operand stage is filled by 32 direct-load instructions of 1 KB (instruction n fills LDS bytes [1024 n, +1024),
+// lane L the 16 bytes at +16 L); wavefront w issues instructions 4w..4w+3.  This returns the byte offset of lane L's 16
+// source bytes from the origin of the stage in global memory, i.e. from element (r = 0, k = first k of the step) of
+// the tensor the instruction reads:
+//   KC: instruction n = rows 8n..8n+7, whole 128-byte lines; LDS row r = 8 chunks of 8 k-values, chunk c at position
+//       c ^ ((r >> 1) & 7).
+//   RC: instruction n = k-rows 4(n/2)..+3, r-half n%2 (128 r-values, from the second tensor when split); inside the
+//       1 KB, k-row j%4 takes 256 bytes = 16 chunks of 8 r-values, chunk c at position c ^ ((j & 3) << 2).
+// The offset does not depend on the step, so one 32-bit register per instruction addresses the whole K loop on top
+// of a scalar base that advances by one step at a time.
 template <bool RC, bool SPLIT>
-__device__ __forceinline__ void tile_sources(const uint16_t* (&src)[4], int (&krow)[4], const TileOperand& op, int tid) {
-  const int wave = tid >> 6, lane = tid & 63;
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const int inst = wave * 4 + i;
-    if (!RC) {
-      const int r = inst * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ ((r >> 1) & 7);
-      const int half = SPLIT ? (r >> 7) : 0;
-      int rr = SPLIT ? (r & 127) : r;
-      rr = rr < op.r_valid ? rr : op.r_valid - 1;
-      src[i] = op.base0 + (half ? op.half_delta : (ptrdiff_t)0) + (size_t)rr * op.ld + c * 8;
-      krow[i] = 0;
-    } else {
-      const int kr = inst * 2 + (lane >> 5);
-      const int c = (lane & 31) ^ ((kr & 3) << 2);
-      const int half = SPLIT ? (c >> 4) : 0;
-      int col = SPLIT ? (c & 15) * 8 : c * 8;
-      col = col < op.r_valid ? col : op.r_valid - 8;
-      src[i] = op.base0 + (half ? op.half_delta : (ptrdiff_t)0) + (size_t)kr * op.ld + col;
-      krow[i] = kr;
-    }
+__device__ __forceinline__ unsigned load_offset(const TileOperand& op, int n, int lane) {
+  static_assert(RC || !SPLIT, "split operands are R-contiguous");
+  if (!RC) {
+    const int r = n * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    const int rr = r < op.r_valid ? r : op.r_valid - 1;
+    return (unsigned)(((size_t)rr * op.ld + c * 8) * 2);
+  } else {
+    const int kr = (n >> 1) * 4 + (lane >> 4);
+    const int c = (lane & 15) ^ ((kr & 3) << 2);
+    int col = c * 8 + ((!SPLIT && (n & 1)) ? 128 : 0);
+    col = col < op.r_valid ? col : op.r_valid - 8;
+    return (unsigned)(((size_t)kr * op.ld + col) * 2);
   }
 }
 
@@ -112,23 +117,36 @@ __device__ __forceinline__ void tile_sources(const uint16_t* (&src)[4], int (&kr
 // Written as inline assembly on purpose: the compiler does not track it, so it never makes the (transposing)
 // fragment reads of the OTHER stage wait for loads still in flight.  The kernel orders these loads itself: an
 // explicit s_waitcnt vmcnt(0) precedes the barrier that publishes a stage, and no compiler-tracked vector-memory
-// load is in flight while these are (the epilogue starts after the last such wait).
+// load is in flight while these are (the epilogue starts after the last such wait).  Two address forms: a 64-bit
+// address per lane, or a scalar base plus a 32-bit byte offset per lane.
 __device__ __forceinline__ void direct_load16(const void* g, const char* lds_dst) {
   const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)lds_dst);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(g) : "memory");
 }
+__device__ __forceinline__ void direct_load16(const void* sbase, unsigned voff, const char* lds_dst) {
+  const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)lds_dst);
+  const unsigned long long b = (unsigned long long)sbase;  // wave-uniform by construction; tell the compiler so
+  const unsigned long long sb = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                                (unsigned)__builtin_amdgcn_readfirstlane((int)b);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds), "v"(voff), "s"(sb) : "memory");
+}
 
-// Issues this thread's 4 direct global->LDS loads of one operand tile for the k-step starting at k0.
-template <bool RC>
-__device__ __forceinline__ void issue_tile(const uint16_t* const (&src)[4], const int (&krow)[4], size_t ld, int k0, int k_end,
-                                           const uint16_t* zero_page, char* lds_tile, int tid) {
-  char* dst = lds_tile + (tid >> 6) * 4096;  // this wavefront's 4 KB of the tile
+// Issues this wavefront's 4 direct loads of one operand stage for the 64 k-values starting at k0 (`delta`: element
+// offset of the pass's tensors from the first pass's).
+template <bool RC, bool SPLIT>
+__device__ __forceinline__ void issue_tile(const unsigned (&voff)[4], const TileOperand& op, ptrdiff_t delta, int k0, int k_end,
+                                           const uint16_t* zero_page, char* lds_tile, int wave, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; i++) {
-    const uint16_t* g;
-    if (!RC) g = src[i] + k0;
-    else g = (k0 + krow[i] < k_end) ? src[i] + (size_t)k0 * ld : zero_page;
-    direct_load16(g, dst + i * 1024);
+    const int n = wave * 4 + i;
+    const uint16_t* sb = ((RC && SPLIT && (n & 1)) ? op.base1 : op.base0) + delta + (RC ? (size_t)k0 * op.ld : (size_t)k0);
+    if (RC && k0 + BK > k_end) {  // the ragged end of K: k-rows past it come from the zeroed page
+      const int kr = (n >> 1) * 4 + (lane >> 4);
+      const char* g = (k0 + kr < k_end) ? reinterpret_cast<const char*>(sb) + voff[i] : reinterpret_cast<const char*>(zero_page);
+      direct_load16(g, lds_tile + n * 1024);
+    } else {
+      direct_load16(sb, voff[i], lds_tile + n * 1024);
+    }
   }
 }
 
@@ -145,11 +163,12 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int r0, int kk, in
     const int p = lane & 15;
     const int k = kk + 8 * (lane >> 5) + (p >> 2);
     const int relem = r0 + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
-    const int c = relem >> 3;
-    const char* a = tile + k * 512 + ((c ^ ((k & 3) << 2)) << 4) + ((relem & 7) << 1);
+    const int c = relem >> 3;  // 0..31: bit 4 = r-half, bits 0..3 = chunk inside the half
+    const char* a = tile + ((((k >> 2) << 1) + (c >> 4)) << 10) + ((k & 3) << 8) + (((c & 15) ^ ((k & 3) << 2)) << 4) +
+                    ((relem & 7) << 1);
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a + 4 * 512));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(a + 2048));  // k + 4: the next group of 4 k-rows
     union { struct { s16x4 lo, hi; } s; bf16x8 v; } u;
     u.s.lo = lo;
     u.s.hi = hi;
@@ -169,9 +188,10 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wp = (wave & 1) * 128;  // p origin of this wavefront
   const int wq = wave >> 1;         // 0..3 along q
+  const int late = wave >> 2;       // wavefronts 4..7 share their SIMDs with 0..3 and load at another time of the step
 
   // ---- block id -> tile (each XCD takes a contiguous run of the logical tile order) ----
   int expert, p_row0 = 0, p_valid, q0_col, k_len;
@@ -234,71 +254,77 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   const int qr0 = (NQ == 2) ? wq * 32 : wq * 64;
   const int qr1 = (NQ == 2) ? 128 + wq * 32 : wq * 64 + 32;
 
+  TileOperand P, Q;
+  ptrdiff_t p_pass_delta = 0, q_pass_delta = 0;  // second K pass (dX): same rows of the second pair of tensors
+  if (KIND == 0) {
+    P.base0 = P.base1 = A.p0 + (size_t)p_row0 * A.p_ld;
+    P.ld = A.p_ld;
+    P.r_valid = p_valid;
+    const uint16_t* qa = A.q0 + (size_t)expert * A.q_expert_stride;
+    Q.base0 = Q.base1 = Q_RC ? qa + q0_col : qa + (size_t)q0_col * A.q_ld;
+    if (NQ == 2) Q.base1 = A.q1 + (size_t)expert * A.q_expert_stride + q0_col;
+    Q.ld = A.q_ld;
+    Q.r_valid = q_valid;
+    if (NPASS == 2) {
+      p_pass_delta = A.p1 - A.p0;
+      q_pass_delta = A.q1 - A.q0;
+    }
+  } else {
+    P.base0 = P.base1 = A.p0 + krow0 * A.p_ld + p_row0;
+    P.ld = A.p_ld;
+    P.r_valid = p_valid;
+    Q.base0 = Q.base1 = A.q0 + krow0 * A.q_ld + q0_col;
+    if (NQ == 2) Q.base1 = A.q1 + krow0 * A.q_ld + q0_col;
+    Q.ld = A.q_ld;
+    Q.r_valid = q_valid;
+  }
+  unsigned pvo[4], qvo[4];
 #pragma unroll
-  for (int pass = 0; pass < NPASS; pass++) {
-    TileOperand P, Q;
-    if (KIND == 0) {
-      const uint16_t* pb = (pass == 0) ? A.p0 : A.p1;
-      P.base0 = pb + (size_t)p_row0 * A.p_ld;
-      P.half_delta = 0;
-      P.ld = A.p_ld;
-      P.r_valid = p_valid;
-      const uint16_t* qa = ((NPASS == 2 && pass == 1) ? A.q1 : A.q0) + (size_t)expert * A.q_expert_stride;
-      const uint16_t* qb = (NQ == 2) ? A.q1 + (size_t)expert * A.q_expert_stride : qa;
-      Q.base0 = Q_RC ? qa + q0_col : qa + (size_t)q0_col * A.q_ld;
-      Q.half_delta = qb - qa;
-      Q.ld = A.q_ld;
-      Q.r_valid = q_valid;
-    } else {
-      P.base0 = A.p0 + krow0 * A.p_ld + p_row0;
-      P.half_delta = 0;
-      P.ld = A.p_ld;
-      P.r_valid = p_valid;
-      Q.base0 = A.q0 + krow0 * A.q_ld + q0_col;
-      Q.half_delta = (NQ == 2) ? A.q1 - A.q0 : (ptrdiff_t)0;
-      Q.ld = A.q_ld;
-      Q.r_valid = q_valid;
-    }
-    const uint16_t* psrc[4];
-    const uint16_t* qsrc[4];
-    int pk[4], qk[4];
-    tile_sources<P_RC, false>(psrc, pk, P, tid);
-    tile_sources<Q_RC, NQ == 2>(qsrc, qk, Q, tid);
-
-    const int nk = (k_len + BK - 1) / BK;
-    if (pass > 0) __syncthreads();  // the previous pass has finished reading both stages
-    if (nk > 0) {
-      issue_tile<P_RC>(psrc, pk, P.ld, 0, k_len, A.zero_page, stage0, tid);
-      issue_tile<Q_RC>(qsrc, qk, Q.ld, 0, k_len, A.zero_page, stage0 + OPERAND_BYTES, tid);
-    }
-    // one k-step: wait for stage `cur`, start filling `nxt` with step kt+1, multiply `cur`
-    auto k_step = [&](const char* cur, char* nxt, int kt) {
-      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this thread's loads of step kt have landed in LDS
-      __syncthreads();                     // ... and everyone's; everyone is also done reading the other stage
-      if (kt + 1 < nk) {
-        issue_tile<P_RC>(psrc, pk, P.ld, (kt + 1) * BK, k_len, A.zero_page, nxt, tid);
-        issue_tile<Q_RC>(qsrc, qk, Q.ld, (kt + 1) * BK, k_len, A.zero_page, nxt + OPERAND_BYTES, tid);
+  for (int i = 0; i < 4; i++) {
+    pvo[i] = load_offset<P_RC, false>(P, wave * 4 + i, lane);
+    qvo[i] = load_offset<Q_RC, NQ == 2>(Q, wave * 4 + i, lane);
+  }
+  const int nk_pass = (k_len + BK - 1) / BK;  // k-steps per K pass
+  const int nk = nk_pass * NPASS;             // k-steps of the whole contraction
+  // this wavefront's 8 direct loads of step j of the contraction
+  auto issue = [&](int j, char* stage) {
+    const bool second = (NPASS == 2) && j >= nk_pass;
+    const int k0 = (second ? j - nk_pass : j) * BK;
+    issue_tile<P_RC, false>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage, wave, lane);
+    issue_tile<Q_RC, NQ == 2>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + OPERAND_BYTES, wave, lane);
+  };
+  if (nk > 0) issue(0, stage0);
+  // One k-step: wait for stage `cur`, multiply it, and meanwhile fill `nxt` with step kt+1.  The two wavefronts of a
+  // SIMD request their share of the next stage at different times of the step (one before its MFMAs, the other
+  // between its two halves of them), so that while one is held up issuing loads the other keeps the matrix pipe busy.
+  auto k_step = [&](const char* cur, char* nxt, int kt) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this thread's loads of step kt have landed in LDS
+    __syncthreads();                     // ... and everyone's; everyone is also done reading the other stage
+    if (late && kt + 1 < nk) issue(kt + 1, nxt);
+    const char* p_lds = cur;
+    const char* q_lds = cur + OPERAND_BYTES;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      if (kk == MOE_EARLY_ISSUE_AT) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (!late && kt + 1 < nk) issue(kt + 1, nxt);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      const char* p_lds = cur;
-      const char* q_lds = cur + OPERAND_BYTES;
+      bf16x8 pf[4], qf[2];
+      qf[0] = read_frag<Q_RC>(q_lds, qr0, kk, lane);
+      qf[1] = read_frag<Q_RC>(q_lds, qr1, kk, lane);
 #pragma unroll
-      for (int kk = 0; kk < BK; kk += 16) {
-        bf16x8 pf[4], qf[2];
-        qf[0] = read_frag<Q_RC>(q_lds, qr0, kk, lane);
-        qf[1] = read_frag<Q_RC>(q_lds, qr1, kk, lane);
+      for (int b = 0; b < 4; b++) pf[b] = read_frag<P_RC>(p_lds, wp + 32 * b, kk, lane);
 #pragma unroll
-        for (int b = 0; b < 4; b++) pf[b] = read_frag<P_RC>(p_lds, wp + 32 * b, kk, lane);
+      for (int b = 0; b < 4; b++)
 #pragma unroll
-        for (int b = 0; b < 4; b++)
-#pragma unroll
-          for (int a = 0; a < 2; a++)
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[a], pf[b], acc[a][b], 0, 0, 0);
-      }
-    };
-    for (int kt = 0; kt < nk; kt += 2) {
-      k_step(stage0, stage1, kt);
-      if (kt + 1 < nk) k_step(stage1, stage0, kt + 1);
+        for (int a = 0; a < 2; a++)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[a], pf[b], acc[a][b], 0, 0, 0);
     }
+  };
+  for (int kt = 0; kt < nk; kt += 2) {
+    k_step(stage0, stage1, kt);
+    if (kt + 1 < nk) k_step(stage1, stage0, kt + 1);
   }
 
   // ---- epilogue.  acc[a][b][v] holds  p = wp + 32b + lane%32,  q (inside the output's tile) =
