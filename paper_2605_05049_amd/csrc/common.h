@@ -12,6 +12,8 @@ namespace moe {
 constexpr int kWave = 64;            // CDNA wavefront width
 constexpr int kMaxExperts = 1024;    // E' limit of the ABI
 constexpr int kPermSlotsPerBlock = 1024;  // slots ranked by one block of the counting sort
+constexpr int kSplitParts = 256;     // K-split parts in flight at most: 32 per XCD (one per CU)
+constexpr int kSplitCounters = 128;  // split tiles at most: 16 per XCD
 constexpr int kMinTileRows = 32;     // smallest row-tile height any GEMM schedule may use
 
 struct Dims {
@@ -48,6 +50,8 @@ struct WsLayout {
   size_t perm_rank, perm_rank_bytes;
   size_t sched, sched_bytes;
   size_t zero_page;
+  size_t splitk_counters;   // kSplitCounters int32: arrivals per split tile
+  size_t splitk_partial;    // kSplitParts fp32 tiles of 256 x 256: partial sums of the tiles whose K range is split
   size_t h, dg, du, nf_bytes;
   size_t total;
 };
@@ -69,6 +73,10 @@ inline WsLayout ws_layout(const Dims& D) {
   off += L.sched_bytes;
   L.zero_page = off;
   off += 256;
+  L.splitk_counters = off;
+  off += round_up((size_t)kSplitCounters * sizeof(int32_t), 256);
+  L.splitk_partial = off;
+  off += (size_t)kSplitParts * 256 * 256 * sizeof(float);
   L.nf_bytes = round_up((size_t)D.N * D.f * sizeof(uint16_t), 256);
   L.h = off; off += L.nf_bytes;
   L.dg = off; off += L.nf_bytes;

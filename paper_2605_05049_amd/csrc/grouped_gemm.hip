@@ -46,6 +46,7 @@ constexpr int OPERAND_BYTES = TILE * BK * 2;    // 32 KB per operand per stage
 constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;  // P + Q
                                                 // two stages = 128 KB of the 160 KB of LDS
 constexpr int kNumXcd = 8;
+constexpr int kCusPerXcd = 32;
 #ifndef MOE_EARLY_ISSUE_AT
 #define MOE_EARLY_ISSUE_AT 32   // k offset inside a step at which wavefronts 0..3 request their share of the next stage
 #endif
@@ -70,6 +71,8 @@ struct GemmArgs {
   int Et;
   int accumulate;
   const uint16_t* zero_page;  // 256 zeroed bytes: source of k-rows past the end of a ragged K
+  float* partial;             // [kSplitParts][256][256] fp32: partial tiles of a split K range
+  int32_t* counters;          // [kSplitCounters], zeroed by the schedule kernel: parts of a split tile that have arrived
   // outputs
   uint16_t* c0; uint16_t* c1; uint16_t* c2; size_t c_ld;   // bf16 outputs (row-major, ld = q_dim)
   const uint16_t* g_in; const uint16_t* u_in;              // saved G, U for the d(SwiGLU) epilogue
@@ -196,13 +199,39 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   // ---- block id -> tile (each XCD takes a contiguous run of the logical tile order) ----
   int expert, p_row0 = 0, p_valid, q0_col, k_len;
   size_t krow0 = 0;
+  // Tail split (bf16-output row-tile problems): when an XCD's last round of tiles would occupy at most half of its
+  // 32 CUs, each of those tiles is cut along K into `split` parts that run side by side; a part writes its fp32
+  // partial tile to the workspace and the part that arrives last adds them up (no part ever waits for another).
+  constexpr bool SPLITK = (KIND == 0 && EPI == EPI_BF16);
+  int split = 1, part = 0, part_slot = 0;
   if (KIND == 0) {
     const int n_row_tiles = A.sched[0];
     const long long total = (long long)n_row_tiles * A.n_q_tiles;
     const long long chunk = (total + kNumXcd - 1) / kNumXcd;
     const long long within = blockIdx.x / kNumXcd;
-    const long long lid = (long long)(blockIdx.x % kNumXcd) * chunk + within;
-    if (within >= chunk || lid >= total) return;
+    const int xcd = blockIdx.x % kNumXcd;
+    const long long lo = (long long)xcd * chunk;
+    const long long cnt = max(min(chunk, total - lo), 0LL);  // tiles of this XCD
+    long long full = cnt;
+    if (SPLITK) {
+      const int rem = (int)(cnt % kCusPerXcd);
+      const int nk_all = ((A.k_dim + BK - 1) / BK) * NPASS;
+      if (rem > 0 && rem <= kCusPerXcd / 2 && nk_all >= 32) {
+        split = min(min(kCusPerXcd / rem, 8), nk_all / 16);
+        full = cnt - rem;
+      }
+    }
+    long long lid;
+    if (within < full) {
+      lid = lo + within;
+      split = 1;
+    } else {
+      const long long u = within - full;
+      if (u >= (cnt - full) * split) return;
+      lid = lo + full + u / split;
+      part = (int)(u % split);
+      part_slot = xcd * kCusPerXcd + (int)u;
+    }
     const int u = (int)(lid / A.n_q_tiles);  // some row tile of the expert this block works for
     expert = A.sched[64 + u];
     const int e_lo = A.offsets[expert], e_hi = A.offsets[expert + 1];
@@ -293,21 +322,24 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     issue_tile<P_RC, false>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage, wave, lane);
     issue_tile<Q_RC, NQ == 2>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + OPERAND_BYTES, wave, lane);
   };
-  if (nk > 0) issue(0, stage0);
+  // the k-steps this block multiplies: all of them, or its part of a split tile
+  const int kt_per = (nk + split - 1) / split;
+  const int kt_begin = part * kt_per, kt_end = min(nk, kt_begin + kt_per);
+  if (kt_begin < kt_end) issue(kt_begin, stage0);
   // One k-step: wait for stage `cur`, multiply it, and meanwhile fill `nxt` with step kt+1.  The two wavefronts of a
   // SIMD request their share of the next stage at different times of the step (one before its MFMAs, the other
   // between its two halves of them), so that while one is held up issuing loads the other keeps the matrix pipe busy.
   auto k_step = [&](const char* cur, char* nxt, int kt) {
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this thread's loads of step kt have landed in LDS
     __syncthreads();                     // ... and everyone's; everyone is also done reading the other stage
-    if (late && kt + 1 < nk) issue(kt + 1, nxt);
+    if (late && kt + 1 < kt_end) issue(kt + 1, nxt);
     const char* p_lds = cur;
     const char* q_lds = cur + OPERAND_BYTES;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       if (kk == MOE_EARLY_ISSUE_AT) {
         __builtin_amdgcn_sched_barrier(0);
-        if (!late && kt + 1 < nk) issue(kt + 1, nxt);
+        if (!late && kt + 1 < kt_end) issue(kt + 1, nxt);
         __builtin_amdgcn_sched_barrier(0);
       }
       bf16x8 pf[4], qf[2];
@@ -322,9 +354,9 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[a], pf[b], acc[a][b], 0, 0, 0);
     }
   };
-  for (int kt = 0; kt < nk; kt += 2) {
+  for (int kt = kt_begin; kt < kt_end; kt += 2) {
     k_step(stage0, stage1, kt);
-    if (kt + 1 < nk) k_step(stage1, stage0, kt + 1);
+    if (kt + 1 < kt_end) k_step(stage1, stage0, kt + 1);
   }
 
   // ---- epilogue.  acc[a][b][v] holds  p = wp + 32b + lane%32,  q (inside the output's tile) =
@@ -338,6 +370,56 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   __syncthreads();                             // every wavefront has finished reading the stages
   char* wlds = ((wave < 4) ? stage0 : stage1) + (wave & 3) * 16384;
   const int q_base = wq * W;                   // first q of this wavefront inside the output's tile
+  if (SPLITK && split > 1) {
+    // ---- a part of a split tile: fp32 partial tile -> workspace, then whoever arrives last reduces
+    float* mine = A.partial + (size_t)part_slot * (TILE * TILE);
+#pragma unroll
+    for (int b = 0; b < 4; b++) {
+#pragma unroll
+      for (int a = 0; a < 2; a++)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; v4++) {
+          const int q = 32 * a + 8 * v4 + 4 * (lane >> 5);
+          float4 r = make_float4(acc[a][b][4 * v4], acc[a][b][4 * v4 + 1], acc[a][b][4 * v4 + 2], acc[a][b][4 * v4 + 3]);
+          *reinterpret_cast<float4*>(wlds + (lane & 31) * PITCH + q * 4) = r;
+        }
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int it = 0; it < 8; it++) {  // 4 rows x 16 lanes x 16 bytes per instruction
+        const int r = it * 4 + (lane >> 4);
+        const int q = (lane & 15) * 4;
+        *reinterpret_cast<float4*>(mine + (size_t)(wp + 32 * b + r) * TILE + q_base + q) =
+            *reinterpret_cast<const float4*>(wlds + r * PITCH + q * 4);
+      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+      __builtin_amdgcn_wave_barrier();
+    }
+    __shared__ int arrived_before;
+    __threadfence();   // this thread's part of the partial tile is visible device-wide ...
+    __syncthreads();   // ... and so is every other thread's, before the arrival is counted
+    if (tid == 0) arrived_before = atomicAdd(A.counters + (part_slot / kCusPerXcd) * (kCusPerXcd / 2) + (part_slot % kCusPerXcd) / split, 1);
+    __syncthreads();
+    if (arrived_before != split - 1) return;
+    __threadfence();   // the other parts' partial tiles, written before their arrivals, are visible to this block
+    const float* parts = A.partial + (size_t)(part_slot - part) * (TILE * TILE);
+#pragma unroll 1
+    for (int it = 0; it < (TILE * TILE / 8) / NTHREADS; it++) {
+      const int idx = it * NTHREADS + tid;
+      const int p = idx >> 5, q = (idx & 31) * 8;
+      if (p < p_valid && q < q_valid) {
+        float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int sp = 0; sp < split; sp++) {
+          const float4 x0 = *reinterpret_cast<const float4*>(parts + (size_t)sp * (TILE * TILE) + p * TILE + q);
+          const float4 x1 = *reinterpret_cast<const float4*>(parts + (size_t)sp * (TILE * TILE) + p * TILE + q + 4);
+          x[0] += x0.x; x[1] += x0.y; x[2] += x0.z; x[3] += x0.w; x[4] += x1.x; x[5] += x1.y; x[6] += x1.z; x[7] += x1.w;
+        }
+        *reinterpret_cast<uint4*>(A.c0 + (size_t)(p_row0 + p) * A.c_ld + q0_col + q) =
+            make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int b = 0; b < 4; b++) {
     // registers -> LDS (fp32), 32 rows x W columns per output tensor (second tensor at +8 KB when NQ == 2)
@@ -434,12 +516,14 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
 }
 
 // Row-tile schedule: one thread per expert.  sched[0] = number of 256-row tiles; sched[64 + u] = expert of tile u;
-// sched[64 + max_tiles + u] = index of that expert's first tile.  The first 64 threads also clear the zero page.
+// sched[64 + max_tiles + u] = index of that expert's first tile.  Also clears the zero page and the split-tile counters.
 __global__ __launch_bounds__(1024) void build_schedule_kernel(const int32_t* __restrict__ offsets, int32_t* __restrict__ sched,
-                                                              uint32_t* __restrict__ zero_page, int Et, int max_tiles) {
+                                                              uint32_t* __restrict__ zero_page, int32_t* __restrict__ counters,
+                                                              int Et, int max_tiles) {
   __shared__ int32_t scan[kMaxExperts];
   const int e = threadIdx.x;
   if (e < 64) zero_page[e] = 0u;
+  if (e < kSplitCounters) counters[e] = 0;
   const int n = (e < Et) ? offsets[e + 1] - offsets[e] : 0;
   const int nt = (n + TILE - 1) / TILE;
   scan[e] = nt;
@@ -463,8 +547,10 @@ __global__ __launch_bounds__(1024) void build_schedule_kernel(const int32_t* __r
 template <int KIND, bool P_RC, bool Q_RC, int NQ, int NPASS, int EPI>
 static int launch_gemm(const char* label, const GemmArgs& A, long long max_blocks, hipStream_t st) {
   auto kern = grouped_gemm_kernel<KIND, P_RC, Q_RC, NQ, NPASS, EPI>;
-  const long long grid = (max_blocks + kNumXcd - 1) / kNumXcd * kNumXcd;
-  if (grid <= 0) return MOE_OK;
+  // bf16-output row-tile problems may cut the tiles of an XCD's last round into up to 32 parts in all
+  const long long per_xcd = (max_blocks + kNumXcd - 1) / kNumXcd + ((KIND == 0 && EPI == EPI_BF16) ? kCusPerXcd : 0);
+  const long long grid = per_xcd * kNumXcd;
+  if (max_blocks <= 0) return MOE_OK;
   MOE_LAUNCH(label, st, kern, dim3((unsigned)grid), dim3(NTHREADS), 0, st, A);
   return MOE_OK;
 }
@@ -501,14 +587,16 @@ extern "C" int moe_grouped_ffn_fwd(const moe_shape* shape, const uint16_t* x_per
   char* wsb = static_cast<char*>(ws);
   int32_t* sched = reinterpret_cast<int32_t*>(wsb + L.sched);
   uint32_t* zero_page = reinterpret_cast<uint32_t*>(wsb + L.zero_page);
+  int32_t* counters = reinterpret_cast<int32_t*>(wsb + L.splitk_counters);
   uint16_t* h = reinterpret_cast<uint16_t*>(wsb + L.h);
   const int max_tiles = (int)sched_max_tiles(D);
   const long long ub_tiles = D.N / TILE + D.Et;  // sum_e ceil(n_e/256) <= N/256 + E'
-  MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, D.Et, max_tiles);
+  MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles);
 
   GemmArgs A = {};
   A.sched = sched; A.max_tiles = max_tiles; A.offsets = offsets; A.Et = D.Et;
   A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
+  A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
   // G, U = X Wg, X Wu ; H = silu(G) * U
   A.n_q_tiles = (D.f + 127) / 128; A.q_dim = D.f; A.k_dim = D.d;
   A.p0 = x_perm; A.p_ld = D.d;
@@ -544,6 +632,7 @@ extern "C" int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_pe
   char* wsb = static_cast<char*>(ws);
   int32_t* sched = reinterpret_cast<int32_t*>(wsb + L.sched);
   uint32_t* zero_page = reinterpret_cast<uint32_t*>(wsb + L.zero_page);
+  int32_t* counters = reinterpret_cast<int32_t*>(wsb + L.splitk_counters);
   uint16_t* h = reinterpret_cast<uint16_t*>(wsb + L.h);
   uint16_t* dg = reinterpret_cast<uint16_t*>(wsb + L.dg);
   uint16_t* du = reinterpret_cast<uint16_t*>(wsb + L.du);
@@ -553,8 +642,9 @@ extern "C" int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_pe
   GemmArgs A = {};
   A.sched = sched; A.max_tiles = max_tiles; A.offsets = offsets; A.Et = D.Et; A.accumulate = accumulate ? 1 : 0;
   A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
+  A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
   if (D.N > 0) {
-    MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, D.Et, max_tiles);
+    MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles);
     // dH = dY Wd^T, then dG, dU and H from the saved G, U
     A.n_q_tiles = (D.f + TILE - 1) / TILE; A.q_dim = D.f; A.k_dim = D.d;
     A.p0 = dy_perm; A.p_ld = D.d;
