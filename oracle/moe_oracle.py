@@ -35,6 +35,52 @@ F64 = np.float64
 
 
 # --------------------------------------------------------------------------------------------------------------
+# the learned gating function's linear map (Section II-A): logits = x W_r^T with one weight row per routed expert
+# --------------------------------------------------------------------------------------------------------------
+def router_logits(x, w_router):
+    """logits[t,e] = <x[t], w_router[e]> for x [T,d], w_router [E,d].  The paper only says the gating function is
+    learned; a bias-free linear map on the token is the reading fixed here (the usual MoE router)."""
+    return np.asarray(x, dtype=F64) @ np.asarray(w_router, dtype=F64).T
+
+
+def router_logits_bwd(x, w_router, dlogits):
+    """Derivative of router_logits: (dx_router [T,d], dw_router [E,d]) for the upstream gradient dlogits [T,E]."""
+    dl = np.asarray(dlogits, dtype=F64)
+    return dl @ np.asarray(w_router, dtype=F64), dl.T @ np.asarray(x, dtype=F64)
+
+
+def router_scales(x, w_router, dlogits):
+    """Quadrature magnitudes of the terms of (logits, dx_router, dw_router), for the element-wise error bound."""
+    x64, w64, dl = np.asarray(x, dtype=F64), np.asarray(w_router, dtype=F64), np.asarray(dlogits, dtype=F64)
+    return (np.sqrt((x64 * x64) @ (w64 * w64).T), np.sqrt((dl * dl) @ (w64 * w64)), np.sqrt((dl * dl).T @ (x64 * x64)))
+
+
+def closed_layer_forward(x, w_router, k, w_gate, w_up, w_down, E_shared=0, renorm=True, logits=None):
+    """The layer closed from x: logits = x W_r^T -> top-k gate -> experts -> combine.  `logits`, when given, replaces
+    the product (used to make the discrete top-k choice from a lower-precision copy of the logits while everything
+    continuous stays in float64).  Returns (out, cache) with cache = (topk_idx, topk_w, probs)."""
+    lg = router_logits(x, w_router) if logits is None else np.asarray(logits, dtype=F64)
+    idx, w, probs = route_topk(lg, k, E_shared, renorm)
+    out, _ = layer_forward(x, idx, w, w_gate, w_up, w_down)
+    return out, (idx, w, probs)
+
+
+def closed_layer_backward(x, w_router, k, w_gate, w_up, w_down, dout, cache, renorm=True):
+    """Gradients of L = sum(out * dout) of closed_layer_forward with the top-k choice held fixed (it is piecewise
+    constant): dx = expert-path term + router term, dw_router, and the three expert weight gradients."""
+    idx, w, probs = cache
+    g = layer_backward(x, idx, w, w_gate, w_up, w_down, dout)
+    dlogits = route_topk_bwd(g["dtopk_w"], idx, w, probs, k, renorm)
+    dx_router, dw_router = router_logits_bwd(x, w_router, dlogits)
+    g = dict(g)
+    g["dlogits"] = dlogits
+    g["dx_router"] = dx_router
+    g["dx_total"] = g["dx"] + dx_router
+    g["dw_router"] = dw_router
+    return g
+
+
+# --------------------------------------------------------------------------------------------------------------
 # routing (Section II-A gating; Section III-A symbols E, E_s, k)
 # --------------------------------------------------------------------------------------------------------------
 

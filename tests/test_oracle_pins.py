@@ -347,6 +347,92 @@ def test_gradients_by_central_finite_differences():
                 assert abs(fd - grad[pos]) <= 1e-6 * max(1.0, abs(grad[pos])), (name, pos, fd, grad[pos])
 
 
+# ---------------------------------------------------------------------------------------------------------
+# the router's linear map and the layer closed from x
+# ---------------------------------------------------------------------------------------------------------
+
+
+def test_router_logits_and_backward_match_loops():
+    rng = np.random.default_rng(5)
+    T, d, E = 4, 5, 3
+    x, wr, dl = rng.standard_normal((T, d)), rng.standard_normal((E, d)), rng.standard_normal((T, E))
+    lg = O.router_logits(x, wr)
+    dxr, dwr = O.router_logits_bwd(x, wr, dl)
+    sl, sx, sw = O.router_scales(x, wr, dl)
+    for t in range(T):
+        for e in range(E):
+            assert abs(lg[t, e] - sum(x[t, i] * wr[e, i] for i in range(d))) < 1e-13
+            assert abs(sl[t, e] - math.sqrt(sum((x[t, i] * wr[e, i]) ** 2 for i in range(d)))) < 1e-13
+    for t in range(T):
+        for i in range(d):
+            assert abs(dxr[t, i] - sum(dl[t, e] * wr[e, i] for e in range(E))) < 1e-13
+            assert abs(sx[t, i] - math.sqrt(sum((dl[t, e] * wr[e, i]) ** 2 for e in range(E)))) < 1e-13
+    for e in range(E):
+        for i in range(d):
+            assert abs(dwr[e, i] - sum(dl[t, e] * x[t, i] for t in range(T))) < 1e-13
+            assert abs(sw[e, i] - math.sqrt(sum((dl[t, e] * x[t, i]) ** 2 for t in range(T)))) < 1e-13
+    # a one-hot token reads out a column of the weight; a one-hot upstream gradient reads out a weight row / a token
+    assert np.array_equal(O.router_logits(np.eye(d)[2:3], wr)[0], wr[:, 2])
+    hot = np.zeros((T, E)); hot[1, 2] = 1.0
+    dxh, dwh = O.router_logits_bwd(x, wr, hot)
+    assert np.array_equal(dxh[1], wr[2]) and not dxh[[0, 2, 3]].any()
+    assert np.array_equal(dwh[2], x[1]) and not dwh[[0, 1]].any()
+
+
+@pytest.mark.parametrize("renorm", [True, False])
+@pytest.mark.parametrize("E_shared", [0, 1])
+def test_closed_layer_against_torch_autograd(renorm, E_shared):
+    """x is the only leaf on the token side: torch's x.grad then holds the expert-path term plus the router term."""
+    x, Wg, Wu, Wd, _, dout = small_case(T=9, d=6, f=5, E=4, k=2, E_shared=E_shared, seed=31)
+    wr = np.random.default_rng(32).standard_normal((4, 6))
+    k = 2
+    out, cache = O.closed_layer_forward(x, wr, k, Wg, Wu, Wd, E_shared, renorm)
+    tx, tg, tu, td, tw = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (x, Wg, Wu, Wd, wr))
+    out_t, top_idx = torch_dense_layer(tx, tg, tu, td, tx @ tw.T, k, E_shared, renorm)
+    assert np.array_equal(top_idx.numpy(), cache[0][:, :k])
+    np.testing.assert_allclose(out, out_t.detach().numpy(), rtol=1e-12, atol=1e-14)
+    (out_t * torch.tensor(dout)).sum().backward()
+    g = O.closed_layer_backward(x, wr, k, Wg, Wu, Wd, dout, cache, renorm)
+    np.testing.assert_allclose(g["dx_total"], tx.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(g["dw_router"], tw.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(g["dw_gate"], tg.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(g["dw_down"], td.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.abs(g["dx_router"]).max() > 1e-3 * np.abs(g["dx"]).max()   # the router term is not negligible here
+    # logits given from outside (e.g. a float32 copy) decide the selection; the continuous part is unchanged
+    out2, cache2 = O.closed_layer_forward(x, wr, k, Wg, Wu, Wd, E_shared, renorm, logits=O.router_logits(x, wr).astype(np.float32))
+    assert np.array_equal(cache2[0], cache[0])
+    np.testing.assert_allclose(out2, out, rtol=1e-6)
+
+
+def test_closed_layer_router_gradients_by_finite_differences():
+    x, Wg, Wu, Wd, _, dout = small_case(T=5, d=4, f=5, E=4, k=2, E_shared=0, seed=41)
+    wr = np.random.default_rng(42).standard_normal((4, 4))
+    out, cache = O.closed_layer_forward(x, wr, 2, Wg, Wu, Wd)
+    g = O.closed_layer_backward(x, wr, 2, Wg, Wu, Wd, dout, cache)
+
+    def loss(x_=x, wr_=wr):
+        o, c = O.closed_layer_forward(x_, wr_, 2, Wg, Wu, Wd)
+        assert np.array_equal(c[0], cache[0])
+        return float((o * dout).sum())
+
+    h = 1e-6
+    for name, arr, grad in (("x_", x, g["dx_total"]), ("wr_", wr, g["dw_router"])):
+        for pos in np.ndindex(arr.shape):
+            ap, am = arr.copy(), arr.copy()
+            ap[pos] += h
+            am[pos] -= h
+            fd = (loss(**{name: ap}) - loss(**{name: am})) / (2 * h)
+            assert abs(fd - grad[pos]) <= 1e-6 * max(1.0, abs(grad[pos])), (name, pos, fd, grad[pos])
+
+
+def test_router_weight_generator_matches_the_logit_recipe():
+    sh = W.MoEShape(T=64, d_model=128, d_ffn=64, E=8, k=2)
+    xb = W.make_tokens(sh, 3)
+    wr = W.bf16_bits_to_f32(W.make_router_weight(sh, 3))
+    assert wr.shape == (8, 128)
+    np.testing.assert_array_equal(O.router_logits(W.bf16_bits_to_f32(xb), wr).astype(np.float32), W.make_router_logits(sh, xb, 3))
+
+
 def test_empty_expert_gets_zero_dw_and_stage_oracles():
     x, Wg, Wu, Wd, logits, dout = small_case(T=9, d=4, f=6, E=5, k=2, seed=4)
     logits[:, 3] = -1e30

@@ -147,6 +147,12 @@ def make_expert_weights(shape: MoEShape, seed: int = 0, std: float = 0.02):
     return wg, wu, wd
 
 
+def make_router_weight(shape: MoEShape, seed: int = 0, std: float = 0.02) -> np.ndarray:
+    """Router weight W_r [E, d_model] (bf16 bits): row e is column e of the matrix make_router_logits multiplies by."""
+    rng = np.random.default_rng([seed, 4])
+    return np.ascontiguousarray(_normal_bf16(rng, (shape.d_model, shape.E), std).T)
+
+
 def make_router_logits(shape: MoEShape, x_bits: np.ndarray, seed: int = 0, bias_std: float = 0.0,
                        std: float = 0.02) -> np.ndarray:
     """logits[T,E] = fp32( x . Wg_router (+ b) ) with Wg_router ~ N(0,std) (bf16) and b_e ~ N(0,bias_std)."""
