@@ -93,6 +93,21 @@ int moe_route_topk(const moe_shape* shape, const float* logits, int32_t* topk_id
 int moe_route_topk_bwd(const moe_shape* shape, const float* dtopk_w, const int32_t* topk_idx,
                        const float* topk_w, const float* probs_save, float* dlogits, void* stream);
 
+/* The learned gating function's linear map (Section II-A): logits[t,e] = <x[t], w_router[e]>.  The paper does not
+ * print the function; a bias-free linear map with one weight row per routed expert is the reading used here.
+ * bf16 operands, fp32 accumulation, fp32 result.
+ *   x [T,d] bf16 in;  w_router [E,d] bf16 in;  logits [T,E] fp32 out. */
+int moe_router_fwd(const moe_shape* shape, const uint16_t* x, const uint16_t* w_router, float* logits,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* Derivative of moe_router_fwd:
+ *   dx_router[t] = sum_e dlogits[t,e] w_router[e]     [T,d] bf16 out (one rounding)
+ *   dw_router[e] = sum_t dlogits[t,e] x[t]            [E,d] fp32, overwritten (accumulate == 0) or added to
+ * dlogits [T,E] fp32 in.  dlogits enters the matrix cores as a bf16 head plus a bf16 remainder (two passes), i.e.
+ * with 16 significand bits; the products accumulate in fp32. */
+int moe_router_bwd(const moe_shape* shape, const uint16_t* x, const uint16_t* w_router, const float* dlogits,
+                   uint16_t* dx_router, float* dw_router, int accumulate, void* ws, size_t ws_bytes, void* stream);
+
 /* Local pack (the per-GPU half of the dispatch of Section III-B: b*s*k rows of d_model bf16 values grouped by
  * expert).  A stable counting sort of the slots by expert id:
  *   counts[e]      = number of slots routed to e                                   [E']   int32 out
@@ -112,6 +127,12 @@ int moe_permute(const moe_shape* shape, const uint16_t* x, const int32_t* topk_i
  * rounding).   dx_perm [N,d] bf16 in;  dx [T,d] bf16 out. */
 int moe_permute_bwd(const moe_shape* shape, const uint16_t* dx_perm, const int32_t* row_of_slot,
                     uint16_t* dx, void* stream);
+
+/* The same with one more addend per token (the router's term of dx when the layer is closed from x):
+ * dx[t] = sum_j dx_perm[row_of_slot[t*K'+j]] + dx_addend[t], fp32 sum (slots in order, then the addend), one bf16
+ * rounding.   dx_addend [T,d] bf16 in. */
+int moe_permute_bwd_add(const moe_shape* shape, const uint16_t* dx_perm, const int32_t* row_of_slot,
+                        const uint16_t* dx_addend, uint16_t* dx, void* stream);
 
 /* Expert FFNs over the ragged per-expert row segments (Section III-A: three matrices per expert, SwiGLU;
  * per-expert token counts s_e).  For expert e over rows [offsets[e], offsets[e+1]):

@@ -13,8 +13,8 @@ _lib = None
 EXPORTED_SYMBOLS = (
     "moe_status_str", "moe_workspace_bytes", "moe_abi_version",
     "moe_profile_enable", "moe_profile_count", "moe_profile_get", "moe_profile_reset",
-    "moe_route_topk", "moe_route_topk_bwd", "moe_permute", "moe_permute_bwd",
-    "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_unpermute_combine_bwd",
+    "moe_route_topk", "moe_route_topk_bwd", "moe_permute", "moe_permute_bwd", "moe_permute_bwd_add",
+    "moe_router_fwd", "moe_router_bwd", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_unpermute_combine_bwd",
 )
 
 
@@ -83,6 +83,9 @@ def load_library():
         "moe_route_topk_bwd": [sp, V, V, V, V, V, V],
         "moe_permute": [sp, V, V, V, V, V, V, V, V, c_size_t, V],
         "moe_permute_bwd": [sp, V, V, V, V],
+        "moe_permute_bwd_add": [sp, V, V, V, V, V],
+        "moe_router_fwd": [sp, V, V, V, V, c_size_t, V],
+        "moe_router_bwd": [sp, V, V, V, V, V, c_int, V, c_size_t, V],
         "moe_grouped_ffn_fwd": [sp, V, V, V, V, V, V, V, V, V, c_size_t, V],
         "moe_grouped_ffn_bwd": [sp, V, V, V, V, V, V, V, V, V, V, V, V, c_int, V, c_size_t, V],
         "moe_unpermute_combine": [sp, V, V, V, V, V],
@@ -211,6 +214,40 @@ def moe_permute_bwd(shape, dx_perm, row_of_slot, dx, stream=None):
         ctypes.byref(s._c), _ptr(dx_perm, bf, s.N * s.d_model, "dx_perm"),
         _ptr(row_of_slot, torch.int32, s.N, "row_of_slot"), _ptr(dx, bf, s.T * s.d_model, "dx"), _stream(stream))
     _check("moe_permute_bwd", rc)
+
+
+def moe_permute_bwd_add(shape, dx_perm, row_of_slot, dx_addend, dx, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    rc = load_library().moe_permute_bwd_add(
+        ctypes.byref(s._c), _ptr(dx_perm, bf, s.N * s.d_model, "dx_perm"),
+        _ptr(row_of_slot, torch.int32, s.N, "row_of_slot"), _ptr(dx_addend, bf, s.T * s.d_model, "dx_addend"),
+        _ptr(dx, bf, s.T * s.d_model, "dx"), _stream(stream))
+    _check("moe_permute_bwd_add", rc)
+
+
+def moe_router_fwd(shape, x, w_router, logits, ws, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    rc = load_library().moe_router_fwd(
+        ctypes.byref(s._c), _ptr(x, bf, s.T * s.d_model, "x"), _ptr(w_router, bf, s.E * s.d_model, "w_router"),
+        _ptr(logits, torch.float32, s.T * s.E, "logits"), _ptr(ws, None, None, "ws"), ws.numel() * ws.element_size(),
+        _stream(stream))
+    _check("moe_router_fwd", rc)
+
+
+def moe_router_bwd(shape, x, w_router, dlogits, dx_router, dw_router, accumulate, ws, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    rc = load_library().moe_router_bwd(
+        ctypes.byref(s._c), _ptr(x, bf, s.T * s.d_model, "x"), _ptr(w_router, bf, s.E * s.d_model, "w_router"),
+        _ptr(dlogits, torch.float32, s.T * s.E, "dlogits"), _ptr(dx_router, bf, s.T * s.d_model, "dx_router"),
+        _ptr(dw_router, torch.float32, s.E * s.d_model, "dw_router"), int(bool(accumulate)),
+        _ptr(ws, None, None, "ws"), ws.numel() * ws.element_size(), _stream(stream))
+    _check("moe_router_bwd", rc)
 
 
 def moe_grouped_ffn_fwd(shape, x_perm, offsets, w_gate, w_up, w_down, y_perm, save_g, save_u, ws, stream=None):

@@ -111,7 +111,7 @@ __device__ __forceinline__ unsigned load_offset(const TileOperand& op, int n, in
     const int kr = (n >> 1) * 4 + (lane >> 4);
     const int c = (lane & 15) ^ ((kr & 3) << 2);
     int col = c * 8 + ((!SPLIT && (n & 1)) ? 128 : 0);
-    col = col < op.r_valid ? col : op.r_valid - 8;
+    col = col < op.r_valid ? col : max(op.r_valid - 8, 0);  // (operands narrower than 8 are padded by their owner)
     return (unsigned)(((size_t)kr * op.ld + col) * 2);
   }
 }
@@ -199,10 +199,10 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   // ---- block id -> tile (each XCD takes a contiguous run of the logical tile order) ----
   int expert, p_row0 = 0, p_valid, q0_col, k_len;
   size_t krow0 = 0;
-  // Tail split (bf16-output row-tile problems): when an XCD's last round of tiles would occupy at most half of its
+  // Tail split (row-tile problems with a plain bf16 or fp32 output): when an XCD's last round of tiles would occupy at most half of its
   // 32 CUs, each of those tiles is cut along K into `split` parts that run side by side; a part writes its fp32
   // partial tile to the workspace and the part that arrives last adds them up (no part ever waits for another).
-  constexpr bool SPLITK = (KIND == 0 && EPI == EPI_BF16);
+  constexpr bool SPLITK = (KIND == 0 && (EPI == EPI_BF16 || EPI == EPI_F32));
   int split = 1, part = 0, part_slot = 0;
   if (KIND == 0) {
     const int n_row_tiles = A.sched[0];
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   TileOperand P, Q;
   ptrdiff_t p_pass_delta = 0, q_pass_delta = 0;  // second K pass (dX): same rows of the second pair of tensors
   if (KIND == 0) {
-    P.base0 = P.base1 = A.p0 + (size_t)p_row0 * A.p_ld;
+    P.base0 = P.base1 = P_RC ? A.p0 + p_row0 : A.p0 + (size_t)p_row0 * A.p_ld;
     P.ld = A.p_ld;
     P.r_valid = p_valid;
     const uint16_t* qa = A.q0 + (size_t)expert * A.q_expert_stride;
@@ -370,6 +370,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   __syncthreads();                             // every wavefront has finished reading the stages
   char* wlds = ((wave < 4) ? stage0 : stage1) + (wave & 3) * 16384;
   const int q_base = wq * W;                   // first q of this wavefront inside the output's tile
+  const bool f32_vector_ok = (A.c_ld & 3) == 0;  // 16-byte fp32 stores need rows that start on 16-byte boundaries
   if (SPLITK && split > 1) {
     // ---- a part of a split tile: fp32 partial tile -> workspace, then whoever arrives last reduces
     float* mine = A.partial + (size_t)part_slot * (TILE * TILE);
@@ -414,8 +415,13 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
           const float4 x1 = *reinterpret_cast<const float4*>(parts + (size_t)sp * (TILE * TILE) + p * TILE + q + 4);
           x[0] += x0.x; x[1] += x0.y; x[2] += x0.z; x[3] += x0.w; x[4] += x1.x; x[5] += x1.y; x[6] += x1.z; x[7] += x1.w;
         }
-        *reinterpret_cast<uint4*>(A.c0 + (size_t)(p_row0 + p) * A.c_ld + q0_col + q) =
-            make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+        if (EPI == EPI_F32) {
+          float* dst = A.f0 + (size_t)expert * A.f_expert_stride + (size_t)(p_row0 + p) * A.c_ld + q0_col + q;
+          for (int i = 0; i < 8 && q + i < q_valid; i++) dst[i] = A.accumulate ? dst[i] + x[i] : x[i];
+        } else {
+          *reinterpret_cast<uint4*>(A.c0 + (size_t)(p_row0 + p) * A.c_ld + q0_col + q) =
+              make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+        }
       }
     }
     return;
@@ -448,11 +454,16 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
           for (int n = 0; n < NQ; n++) {
             float4 v = *reinterpret_cast<const float4*>(wlds + n * 8192 + r * PITCH + q * 4);
             float* dst = (n == 0 ? A.f0 : A.f1) + o;
-            if (A.accumulate) {
-              const float4 old = *reinterpret_cast<const float4*>(dst);
-              v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+            if (f32_vector_ok && q_base + q + 4 <= q_valid) {
+              if (A.accumulate) {
+                const float4 old = *reinterpret_cast<const float4*>(dst);
+                v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+              }
+              *reinterpret_cast<float4*>(dst) = v;
+            } else {  // a row pitch or a width that is not a multiple of 4 (router logits with odd E): element-wise
+              const float e4[4] = {v.x, v.y, v.z, v.w};
+              for (int i = 0; i < 4 && q_base + q + i < q_valid; i++) dst[i] = A.accumulate ? dst[i] + e4[i] : e4[i];
             }
-            *reinterpret_cast<float4*>(dst) = v;
           }
         }
       }
@@ -544,11 +555,31 @@ __global__ __launch_bounds__(1024) void build_schedule_kernel(const int32_t* __r
   }
 }
 
+// Router helpers.  Writes the two one-segment offset arrays ({0, T} for problems whose rows are tokens, {0, E} for the
+// one whose rows are experts) and, when dlogits is given, splits it into a bf16 head and a bf16 remainder
+// (hi = bf16(v), lo = bf16(v - hi): hi + lo carries 16 significand bits of v), zero-padded to Epad columns.
+__global__ __launch_bounds__(256) void router_prepare_kernel(const float* __restrict__ dlogits, uint16_t* __restrict__ hi,
+                                                             uint16_t* __restrict__ lo, int32_t* __restrict__ offsets2,
+                                                             int T, int E, int Epad) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i == 0) {
+    offsets2[0] = 0; offsets2[1] = T;
+    offsets2[4] = 0; offsets2[5] = E;
+  }
+  if (dlogits == nullptr || i >= (long long)T * Epad) return;
+  const int t = (int)(i / Epad), e = (int)(i % Epad);
+  const float v = e < E ? dlogits[(size_t)t * E + e] : 0.f;
+  const uint32_t h2 = pack_bf16(v, 0.f) & 0xFFFFu;
+  const float hf = bf16lo(h2);
+  hi[i] = (uint16_t)h2;
+  lo[i] = (uint16_t)(pack_bf16(v - hf, 0.f) & 0xFFFFu);
+}
+
 template <int KIND, bool P_RC, bool Q_RC, int NQ, int NPASS, int EPI>
 static int launch_gemm(const char* label, const GemmArgs& A, long long max_blocks, hipStream_t st) {
   auto kern = grouped_gemm_kernel<KIND, P_RC, Q_RC, NQ, NPASS, EPI>;
   // bf16-output row-tile problems may cut the tiles of an XCD's last round into up to 32 parts in all
-  const long long per_xcd = (max_blocks + kNumXcd - 1) / kNumXcd + ((KIND == 0 && EPI == EPI_BF16) ? kCusPerXcd : 0);
+  const long long per_xcd = (max_blocks + kNumXcd - 1) / kNumXcd + ((KIND == 0 && (EPI == EPI_BF16 || EPI == EPI_F32)) ? kCusPerXcd : 0);
   const long long grid = per_xcd * kNumXcd;
   if (max_blocks <= 0) return MOE_OK;
   MOE_LAUNCH(label, st, kern, dim3((unsigned)grid), dim3(NTHREADS), 0, st, A);
@@ -670,5 +701,89 @@ extern "C" int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_pe
   A.q0 = dg; A.q1 = du; A.q_ld = D.f;
   A.f0 = dw_gate; A.f1 = dw_up; A.f_expert_stride = (size_t)D.d * D.f; A.c_ld = D.f;
   MOE_TRY((launch_gemm<1, true, true, 2, 1, EPI_F32>("ffn_bwd_dw_gate_up", A, (long long)D.Et * ((A.n_p_tiles + 7) / 8) * ((A.n_q_tiles + 3) / 4) * 32, st)));
+  return launch_status();
+}
+
+extern "C" int moe_router_fwd(const moe_shape* shape, const uint16_t* x, const uint16_t* w_router, float* logits,
+                              void* ws, size_t ws_bytes, void* stream) {
+  using namespace moe;
+  Dims D;
+  WsLayout L;
+  int rc = common_checks(shape, &D, ws, ws_bytes, &L);
+  if (rc != MOE_OK) return rc;
+  MOE_REQUIRE_PTR(x); MOE_REQUIRE_PTR(w_router); MOE_REQUIRE_PTR(logits);
+  MOE_REQUIRE_ALIGNED(x); MOE_REQUIRE_ALIGNED(w_router); MOE_REQUIRE_ALIGNED(logits);
+  if (D.T == 0) return MOE_OK;
+  hipStream_t st = (hipStream_t)stream;
+  char* wsb = static_cast<char*>(ws);
+  int32_t* sched = reinterpret_cast<int32_t*>(wsb + L.sched);
+  uint32_t* zero_page = reinterpret_cast<uint32_t*>(wsb + L.zero_page);
+  int32_t* counters = reinterpret_cast<int32_t*>(wsb + L.splitk_counters);
+  int32_t* offs = reinterpret_cast<int32_t*>(wsb + L.router_offsets);
+  const int max_tiles = (int)sched_max_tiles(D);
+  MOE_LAUNCH("router_prepare", st, router_prepare_kernel, dim3(1), dim3(256), 0, st, (const float*)nullptr, (uint16_t*)nullptr,
+             (uint16_t*)nullptr, offs, (int)D.T, (int)D.E, 0);
+  MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs, sched, zero_page, counters, 1, max_tiles);
+  GemmArgs A = {};
+  A.sched = sched; A.max_tiles = max_tiles; A.offsets = offs; A.Et = 1;
+  A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
+  A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
+  // logits[T,E] = X W_r^T: rows = tokens, columns = experts, K = d; both operands K-contiguous
+  A.n_q_tiles = (D.E + TILE - 1) / TILE; A.q_dim = D.E; A.k_dim = D.d;
+  A.p0 = x; A.p_ld = D.d;
+  A.q0 = w_router; A.q_ld = D.d; A.q_expert_stride = 0;
+  A.f0 = logits; A.f_expert_stride = 0; A.c_ld = D.E;
+  const long long row_tiles = (D.T + TILE - 1) / TILE;
+  MOE_TRY((launch_gemm<0, false, false, 1, 1, EPI_F32>("router_fwd", A, row_tiles * A.n_q_tiles, st)));
+  return launch_status();
+}
+
+extern "C" int moe_router_bwd(const moe_shape* shape, const uint16_t* x, const uint16_t* w_router, const float* dlogits,
+                              uint16_t* dx_router, float* dw_router, int accumulate, void* ws, size_t ws_bytes, void* stream) {
+  using namespace moe;
+  Dims D;
+  WsLayout L;
+  int rc = common_checks(shape, &D, ws, ws_bytes, &L);
+  if (rc != MOE_OK) return rc;
+  MOE_REQUIRE_PTR(x); MOE_REQUIRE_PTR(w_router); MOE_REQUIRE_PTR(dlogits); MOE_REQUIRE_PTR(dx_router); MOE_REQUIRE_PTR(dw_router);
+  MOE_REQUIRE_ALIGNED(x); MOE_REQUIRE_ALIGNED(w_router); MOE_REQUIRE_ALIGNED(dlogits); MOE_REQUIRE_ALIGNED(dx_router);
+  MOE_REQUIRE_ALIGNED(dw_router);
+  if (D.T == 0) return MOE_OK;
+  hipStream_t st = (hipStream_t)stream;
+  char* wsb = static_cast<char*>(ws);
+  int32_t* sched = reinterpret_cast<int32_t*>(wsb + L.sched);
+  uint32_t* zero_page = reinterpret_cast<uint32_t*>(wsb + L.zero_page);
+  int32_t* counters = reinterpret_cast<int32_t*>(wsb + L.splitk_counters);
+  int32_t* offs = reinterpret_cast<int32_t*>(wsb + L.router_offsets);
+  uint16_t* dl_hi = reinterpret_cast<uint16_t*>(wsb + L.dl_hi);
+  uint16_t* dl_lo = reinterpret_cast<uint16_t*>(wsb + L.dl_lo);
+  const int max_tiles = (int)sched_max_tiles(D);
+  const int Epad = (int)round_up((size_t)D.E, 64);
+  const long long n_split = (long long)D.T * Epad;
+  MOE_LAUNCH("router_prepare", st, router_prepare_kernel, dim3((unsigned)((n_split + 255) / 256)), dim3(256), 0, st, dlogits, dl_hi, dl_lo,
+             offs, (int)D.T, (int)D.E, Epad);
+  GemmArgs A = {};
+  A.sched = sched; A.max_tiles = max_tiles; A.Et = 1; A.accumulate = 0;
+  A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
+  A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
+  // dx_router[T,d] = dlogits W_r: rows = tokens, columns = d, K = E in two passes (head, remainder of dlogits);
+  // P K-contiguous in the padded copies, Q = W_r read with k = expert row (R-contiguous, rows past E are zeros)
+  MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs, sched, zero_page, counters, 1, max_tiles);
+  A.offsets = offs;
+  A.n_q_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.d; A.k_dim = D.E;
+  A.p0 = dl_hi; A.p1 = dl_lo; A.p_ld = Epad;
+  A.q0 = w_router; A.q1 = w_router; A.q_ld = D.d; A.q_expert_stride = 0;
+  A.c0 = dx_router; A.c_ld = D.d;
+  const long long row_tiles = (D.T + TILE - 1) / TILE;
+  MOE_TRY((launch_gemm<0, false, true, 1, 2, EPI_BF16>("router_bwd_dx", A, row_tiles * A.n_q_tiles, st)));
+  // dw_router[E,d] = dlogits^T X: rows = experts, columns = d, K = T in two passes; both operands R-contiguous
+  MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs + 4, sched, zero_page, counters, 1, max_tiles);
+  A.offsets = offs + 4; A.accumulate = accumulate ? 1 : 0;
+  A.n_q_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.d; A.k_dim = (int)D.T;
+  A.p0 = dl_hi; A.p1 = dl_lo; A.p_ld = Epad;
+  A.q0 = x; A.q1 = x; A.q_ld = D.d; A.q_expert_stride = 0;
+  A.c0 = nullptr; A.f0 = dw_router; A.f_expert_stride = 0; A.c_ld = D.d;
+  const long long e_tiles = (D.E + TILE - 1) / TILE;
+  MOE_TRY((launch_gemm<0, true, true, 1, 2, EPI_F32>("router_bwd_dw", A, e_tiles * A.n_q_tiles, st)));
   return launch_status();
 }

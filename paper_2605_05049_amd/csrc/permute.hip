@@ -224,8 +224,8 @@ __device__ __forceinline__ u32x4 pack8(const float (&a)[8]) {
 
 template <int KP, bool UNIT>
 __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ y, const int32_t* __restrict__ row_of_slot,
-                                                      const float* __restrict__ topk_w, u32x4* __restrict__ out, int T, int Kp,
-                                                      int dvec) {
+                                                      const float* __restrict__ topk_w, const u32x4* __restrict__ addend,
+                                                      u32x4* __restrict__ out, int T, int Kp, int dvec) {
   const int lane = threadIdx.x % kWave;
   const int t = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + threadIdx.x / kWave);
   if (t >= T) return;
@@ -256,6 +256,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
           float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int j = 0; j < KP; j++) fma_bf16x8(acc, val[i][j], w[j]);  // slot order, fp32
+          if (addend) fma_bf16x8(acc, addend[(size_t)t * dvec + v], 1.0f);
           st_row<kCombineNT>(dst + v, pack8(acc));
         }
       }
@@ -266,6 +267,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
     for (int v = lane; v < dvec; v += kWave) {
       float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       for (int j = 0; j < Kp; j++) fma_bf16x8(acc, y[(size_t)rows[j] * dvec + v], UNIT ? 1.0f : w[j]);
+      if (addend) fma_bf16x8(acc, addend[(size_t)t * dvec + v], 1.0f);
       st_row<kCombineNT>(dst + v, pack8(acc));
     }
   }
@@ -400,7 +402,23 @@ extern "C" int moe_permute_bwd(const moe_shape* shape, const uint16_t* dx_perm, 
   hipStream_t st = (hipStream_t)stream;
   MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("permute_bwd", st, (combine_kernel<KP, true>), dim3((D.T + 3) / 4), dim3(256), 0, st,
                                    reinterpret_cast<const u32x4*>(dx_perm), row_of_slot, (const float*)nullptr,
-                                   reinterpret_cast<u32x4*>(dx), D.T, D.Kp, D.d / 8));
+                                   (const u32x4*)nullptr, reinterpret_cast<u32x4*>(dx), D.T, D.Kp, D.d / 8));
+  return launch_status();
+}
+
+extern "C" int moe_permute_bwd_add(const moe_shape* shape, const uint16_t* dx_perm, const int32_t* row_of_slot,
+                                   const uint16_t* dx_addend, uint16_t* dx, void* stream) {
+  using namespace moe;
+  Dims D;
+  int rc = check_shape(shape, &D);
+  if (rc != MOE_OK) return rc;
+  MOE_REQUIRE_PTR(dx_perm); MOE_REQUIRE_PTR(row_of_slot); MOE_REQUIRE_PTR(dx_addend); MOE_REQUIRE_PTR(dx);
+  MOE_REQUIRE_ALIGNED(dx_perm); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(dx_addend); MOE_REQUIRE_ALIGNED(dx);
+  if (D.T == 0) return MOE_OK;
+  hipStream_t st = (hipStream_t)stream;
+  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("permute_bwd_add", st, (combine_kernel<KP, true>), dim3((D.T + 3) / 4), dim3(256), 0, st,
+                                   reinterpret_cast<const u32x4*>(dx_perm), row_of_slot, (const float*)nullptr,
+                                   reinterpret_cast<const u32x4*>(dx_addend), reinterpret_cast<u32x4*>(dx), D.T, D.Kp, D.d / 8));
   return launch_status();
 }
 
@@ -415,8 +433,8 @@ extern "C" int moe_unpermute_combine(const moe_shape* shape, const uint16_t* y_p
   if (D.T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
   MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("unpermute_combine", st, (combine_kernel<KP, false>), dim3((D.T + 3) / 4), dim3(256), 0, st,
-                                   reinterpret_cast<const u32x4*>(y_perm), row_of_slot, topk_w, reinterpret_cast<u32x4*>(out),
-                                   D.T, D.Kp, D.d / 8));
+                                   reinterpret_cast<const u32x4*>(y_perm), row_of_slot, topk_w, (const u32x4*)nullptr,
+                                   reinterpret_cast<u32x4*>(out), D.T, D.Kp, D.d / 8));
   return launch_status();
 }
 

@@ -39,12 +39,21 @@ class MoeLayerBuffers:
             self.dw_up = e(Et, d, f, dtype=f32)
             self.dw_down = e(Et, f, d, dtype=f32)
             self.dlogits = e(T, s.E, dtype=f32) if with_router else None
+        # the layer closed from x (router weight given): logits, the router's term of dx, the router weight gradient
+        self.logits = e(T, s.E, dtype=f32) if with_router else None
+        if with_backward and with_router:
+            self.dx_router = e(T, d, dtype=bf)
+            self.dw_router = e(s.E, d, dtype=f32)
 
 
-def layer_forward(buf: MoeLayerBuffers, x, w_gate, w_up, w_down, logits=None, stream=None):
+def layer_forward(buf: MoeLayerBuffers, x, w_gate, w_up, w_down, logits=None, w_router=None, stream=None):
     """routing (skipped when logits is None: buf.topk_idx / buf.topk_w were filled by the caller, as for an
-    expert-parallel shard) -> permute -> grouped FFN -> combine.  Returns buf.out."""
+    expert-parallel shard) -> permute -> grouped FFN -> combine.  With `w_router` the logits are computed first
+    (buf.logits = x W_r^T).  Returns buf.out."""
     s = buf.shape
+    if w_router is not None:
+        B.moe_router_fwd(s, x, w_router, buf.logits, buf.ws, stream)
+        logits = buf.logits
     if logits is not None:
         B.moe_route_topk(s, logits, buf.topk_idx, buf.topk_w, buf.probs, stream)
     B.moe_permute(s, x, buf.topk_idx, buf.x_perm, buf.counts, buf.offsets, buf.row_of_slot, buf.slot_of_row, buf.ws, stream)
@@ -53,10 +62,20 @@ def layer_forward(buf: MoeLayerBuffers, x, w_gate, w_up, w_down, logits=None, st
     return buf.out
 
 
-def layer_backward(buf: MoeLayerBuffers, dout, w_gate, w_up, w_down, accumulate=False, with_router=True, stream=None):
+def layer_backward(buf: MoeLayerBuffers, dout, w_gate, w_up, w_down, accumulate=False, with_router=True, x=None,
+                   w_router=None, stream=None):
     """combine_bwd -> grouped FFN bwd -> permute_bwd -> route_bwd.  Results land in buf.dx, buf.dw_*, buf.dtopk_w,
-    buf.dlogits."""
+    buf.dlogits.  With `x` and `w_router` the layer is closed from x: route_bwd -> router_bwd come before the
+    un-permutation, buf.dx then holds the expert-path term plus the router's term, and buf.dw_router is filled."""
     s = buf.shape
+    if w_router is not None:
+        B.moe_unpermute_combine_bwd(s, dout, buf.y_perm, buf.row_of_slot, buf.topk_w, buf.dy_perm, buf.dtopk_w, stream)
+        B.moe_grouped_ffn_bwd(s, buf.dy_perm, buf.x_perm, buf.offsets, w_gate, w_up, w_down, buf.save_g, buf.save_u,
+                              buf.dx_perm, buf.dw_gate, buf.dw_up, buf.dw_down, accumulate, buf.ws, stream)
+        B.moe_route_topk_bwd(s, buf.dtopk_w, buf.topk_idx, buf.topk_w, buf.probs, buf.dlogits, stream)
+        B.moe_router_bwd(s, x, w_router, buf.dlogits, buf.dx_router, buf.dw_router, accumulate, buf.ws, stream)
+        B.moe_permute_bwd_add(s, buf.dx_perm, buf.row_of_slot, buf.dx_router, buf.dx, stream)
+        return
     B.moe_unpermute_combine_bwd(s, dout, buf.y_perm, buf.row_of_slot, buf.topk_w, buf.dy_perm, buf.dtopk_w, stream)
     B.moe_grouped_ffn_bwd(s, buf.dy_perm, buf.x_perm, buf.offsets, w_gate, w_up, w_down, buf.save_g, buf.save_u,
                           buf.dx_perm, buf.dw_gate, buf.dw_up, buf.dw_down, accumulate, buf.ws, stream)

@@ -82,6 +82,14 @@ def test_argument_checks_run_before_any_launch(lib):
     assert lib.moe_unpermute_combine(sp, FAKE, FAKE, None, FAKE, None) == -1
     assert lib.moe_unpermute_combine(sp, FAKE, FAKE, ODD, FAKE, None) == -3
     assert lib.moe_unpermute_combine_bwd(sp, FAKE, FAKE, FAKE, FAKE, FAKE, None, None) == -1
+    assert lib.moe_permute_bwd_add(sp, FAKE, FAKE, None, FAKE, None) == -1
+    assert lib.moe_permute_bwd_add(sp, FAKE, FAKE, ODD, FAKE, None) == -3
+    assert lib.moe_router_fwd(sp, FAKE, None, FAKE, FAKE, 1 << 40, None) == -1
+    assert lib.moe_router_fwd(sp, FAKE, FAKE, FAKE, FAKE, 16, None) == -4
+    assert lib.moe_router_fwd(bad, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == -2
+    assert lib.moe_router_bwd(sp, FAKE, FAKE, FAKE, FAKE, None, 0, FAKE, 1 << 40, None) == -1
+    assert lib.moe_router_bwd(sp, FAKE, FAKE, ODD, FAKE, FAKE, 0, FAKE, 1 << 40, None) == -3
+    assert lib.moe_router_bwd(sp, FAKE, FAKE, FAKE, FAKE, FAKE, 0, None, 0, None) == -1
 
 
 def test_binding_rejects_host_tensors(lib):
