@@ -189,6 +189,59 @@ def run_streaming_bench(moe, W, steps):
     return out
 
 
+def run_router_bench(moe, W, workload, steps):
+    """The router's three GEMMs (logits = x W_r^T, its dx term, dW_r) on the workload's shape, each call timed in its
+    own loop; they are skinny (E columns), so the bound is the HBM traffic of x, not the matrix cores."""
+    import numpy as np
+    import torch
+    sh = W.WORKLOADS[workload].shape
+    s = moe.Shape.of(sh)
+    T, d, E = s.T, s.d_model, s.E
+    x = dev_bf16(W.make_tokens(sh, seed=0))
+    wr = dev_bf16(W.make_router_weight(sh, seed=0))
+    dl = torch.from_numpy((np.random.default_rng(5).standard_normal((T, E)) * 0.1).astype(np.float32)).cuda()
+    logits = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    dxr = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+    dwr = torch.empty((E, d), dtype=torch.float32, device="cuda")
+    ws = torch.empty(moe.workspace_bytes(s), dtype=torch.uint8, device="cuda")
+    calls = {"moe_router_fwd": lambda: moe.moe_router_fwd(s, x, wr, logits, ws),
+             "moe_router_bwd": lambda: moe.moe_router_bwd(s, x, wr, dl, dxr, dwr, 0, ws)}
+    alg = {"router_fwd": T * d * 2 + E * d * 2 + T * E * 4,                    # read x and W_r, write logits
+           "router_bwd_dx": T * E * 4 + E * d * 2 + T * d * 2,                 # read dlogits and W_r, write dx
+           "router_bwd_dw": T * E * 4 + T * d * 2 + E * d * 4}                 # read dlogits and x, write dW_r
+    out = {"workload": f"{workload}: T={T} d={d} E={E}", "calls": {}, "kernels": {}}
+    for name, fn in calls.items():
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out["calls"][name] = {"avg_us": round(e0.elapsed_time(e1) / steps * 1e3, 1)}
+        moe.profile_reset()
+        moe.profile_enable(True)
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        moe.profile_enable(False)
+        per = {}
+        for kn, ms in moe.profile_records():
+            per.setdefault(kn, []).append(ms)
+        moe.profile_reset()
+        for kn, v in per.items():
+            avg = sum(v) / len(v)
+            ent = {"avg_us": round(avg * 1e3, 1), "launches": len(v) // steps}
+            if kn in alg:
+                ent["algorithmic_MB"] = round(alg[kn] / 1e6, 1)
+                ent["GBs"] = round(alg[kn] / (avg * 1e-3) / 1e9, 1)
+                ent["frac_hbm_peak"] = round(alg[kn] / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+            out["kernels"][kn] = ent
+    return out
+
+
 def run_copy_calibration():
     """A plain device-to-device copy of known size (512 MiB read + 512 MiB written per launch, 5 launches): the yard
     stick the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by."""
@@ -294,6 +347,8 @@ def main():
     }
     if not args.no_streaming:
         res["permute_combine"] = run_streaming_bench(moe, W, steps=20)
+    if not args.no_streaming and args.workload != "shard":
+        res["router"] = run_router_bench(moe, W, args.workload, steps=20)
     if args.copy_calibration:
         res["copy_calibration"] = run_copy_calibration()
     if not args.no_cpu_baseline:

@@ -136,12 +136,16 @@ __device__ __forceinline__ void direct_load16(const void* sbase, unsigned voff, 
 
 // Issues this wavefront's 4 direct loads of one operand stage for the 64 k-values starting at k0 (`delta`: element
 // offset of the pass's tensors from the first pass's).
-template <bool RC, bool SPLIT>
+template <bool RC, bool SPLIT, bool NARROW = false>
 __device__ __forceinline__ void issue_tile(const unsigned (&voff)[4], const TileOperand& op, ptrdiff_t delta, int k0, int k_end,
                                            const uint16_t* zero_page, char* lds_tile, int wave, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const int n = wave * 4 + i;
+    // NARROW (the router's skinny problems): instructions that would only fetch rows or columns past the operand's
+    // valid extent are left out; those LDS rows then hold stale data, which only ever reaches accumulators that are
+    // never stored (an accumulator row or column depends on its own operand row alone)
+    if (NARROW && (RC ? (!SPLIT && (n & 1) && op.r_valid <= 128) : n * 8 >= op.r_valid)) continue;
     const uint16_t* sb = ((RC && SPLIT && (n & 1)) ? op.base1 : op.base0) + delta + (RC ? (size_t)k0 * op.ld : (size_t)k0);
     if (RC && k0 + BK > k_end) {  // the ragged end of K: k-rows past it come from the zeroed page
       const int kr = (n >> 1) * 4 + (lane >> 4);
@@ -203,6 +207,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   // 32 CUs, each of those tiles is cut along K into `split` parts that run side by side; a part writes its fp32
   // partial tile to the workspace and the part that arrives last adds them up (no part ever waits for another).
   constexpr bool SPLITK = (KIND == 0 && (EPI == EPI_BF16 || EPI == EPI_F32));
+  constexpr bool NARROW = (KIND == 0 && EPI == EPI_F32);  // fp32-output row-tile problems are the router's: E rows or columns
   int split = 1, part = 0, part_slot = 0;
   if (KIND == 0) {
     const int n_row_tiles = A.sched[0];
@@ -319,8 +324,8 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   auto issue = [&](int j, char* stage) {
     const bool second = (NPASS == 2) && j >= nk_pass;
     const int k0 = (second ? j - nk_pass : j) * BK;
-    issue_tile<P_RC, false>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage, wave, lane);
-    issue_tile<Q_RC, NQ == 2>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + OPERAND_BYTES, wave, lane);
+    issue_tile<P_RC, false, NARROW>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage, wave, lane);
+    issue_tile<Q_RC, NQ == 2, NARROW>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + OPERAND_BYTES, wave, lane);
   };
   // the k-steps this block multiplies: all of them, or its part of a split tile
   const int kt_per = (nk + split - 1) / split;
@@ -390,8 +395,9 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
       for (int it = 0; it < 8; it++) {  // 4 rows x 16 lanes x 16 bytes per instruction
         const int r = it * 4 + (lane >> 4);
         const int q = (lane & 15) * 4;
-        *reinterpret_cast<float4*>(mine + (size_t)(wp + 32 * b + r) * TILE + q_base + q) =
-            *reinterpret_cast<const float4*>(wlds + r * PITCH + q * 4);
+        if (wp + 32 * b + r < p_valid && q_base + q < q_valid)   // (the reduction reads only valid rows and columns)
+          *reinterpret_cast<float4*>(mine + (size_t)(wp + 32 * b + r) * TILE + q_base + q) =
+              *reinterpret_cast<const float4*>(wlds + r * PITCH + q * 4);
       }
       __builtin_amdgcn_s_waitcnt(0xC07F);
       __builtin_amdgcn_wave_barrier();
