@@ -71,7 +71,7 @@ inline WsLayout ws_layout(const Dims& D) {
   L.perm_rank_bytes = round_up((size_t)D.N * sizeof(int32_t) + 256, 256);
   off += L.perm_rank_bytes;
   L.sched = off;
-  L.sched_bytes = round_up((size_t)(64 + 2 * sched_max_tiles(D)) * sizeof(int32_t), 256);
+  L.sched_bytes = round_up((size_t)(64 + 2 * sched_max_tiles(D) + kMaxExperts) * sizeof(int32_t), 256);
   off += L.sched_bytes;
   L.zero_page = off;
   off += 256;

@@ -253,16 +253,17 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     // Tiles of an expert are walked in 8 x 4 super-tiles (8 along p, 4 along q = the 32 tiles one XCD runs at a
     // time): each p panel then meets 4 q panels and each q panel 8 p panels in that XCD's L2 instead of one
     // panel being re-fetched for every tile of the other dimension.  The grid is padded to whole super-tiles.
+    // A tile's duration is proportional to its expert's row count, so the super-tiles are dealt round-robin to the
+    // XCDs (not in contiguous runs, which would hand a whole large expert to one XCD), experts with the most rows
+    // first (the tail of the launch is then made of short tiles).
     const int sp = (A.n_p_tiles + 7) / 8, sq = (A.n_q_tiles + 3) / 4;
-    const long long per_e = (long long)sp * sq * 32;
-    const long long total = per_e * A.Et;
-    const long long chunk = (total + kNumXcd - 1) / kNumXcd;
+    const int supers_per_e = sp * sq;
+    const long long n_super = (long long)supers_per_e * A.Et;
     const long long within = blockIdx.x / kNumXcd;
-    const long long lid = (long long)(blockIdx.x % kNumXcd) * chunk + within;
-    if (within >= chunk || lid >= total) return;
-    expert = (int)(lid / per_e);
-    const int local = (int)(lid % per_e);
-    const int super = local >> 5, in_super = local & 31;
+    const long long sid = (within >> 5) * kNumXcd + (blockIdx.x % kNumXcd);
+    if (sid >= n_super) return;
+    expert = A.sched[64 + 2 * A.max_tiles + (int)(sid / supers_per_e)];  // the (sid / supers_per_e)-th largest expert
+    const int super = (int)(sid % supers_per_e), in_super = (int)(within & 31);
     const int pt = (super % sp) * 8 + (in_super & 7);
     const int qt = (super / sp) * 4 + (in_super >> 3);
     if (pt >= A.n_p_tiles || qt >= A.n_q_tiles) return;  // padding of the super-tile grid
@@ -533,7 +534,8 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
 }
 
 // Row-tile schedule: one thread per expert.  sched[0] = number of 256-row tiles; sched[64 + u] = expert of tile u;
-// sched[64 + max_tiles + u] = index of that expert's first tile.  Also clears the zero page and the split-tile counters.
+// sched[64 + max_tiles + u] = index of that expert's first tile; sched[64 + 2 max_tiles + i] = expert with the i-th most rows.
+// Also clears the zero page and the split-tile counters.
 __global__ __launch_bounds__(1024) void build_schedule_kernel(const int32_t* __restrict__ offsets, int32_t* __restrict__ sched,
                                                               uint32_t* __restrict__ zero_page, int32_t* __restrict__ counters,
                                                               int Et, int max_tiles) {
@@ -553,6 +555,15 @@ __global__ __launch_bounds__(1024) void build_schedule_kernel(const int32_t* __r
   }
   const int first = scan[e] - nt;
   if (e == kMaxExperts - 1) sched[0] = scan[e];
+  // experts by descending row count (ties: lower id first): sched[64 + 2 max_tiles + rank] = expert
+  __shared__ int32_t rows_of[kMaxExperts];
+  rows_of[e] = (e < Et) ? n : -1;
+  __syncthreads();
+  if (e < Et) {
+    int rank = 0;
+    for (int o = 0; o < Et; o++) rank += (rows_of[o] > n) || (rows_of[o] == n && o < e);
+    sched[64 + 2 * max_tiles + rank] = e;
+  }
   for (int i = 0; i < nt; i++) {
     if (first + i < max_tiles) {
       sched[64 + first + i] = e;
@@ -579,6 +590,12 @@ __global__ __launch_bounds__(256) void router_prepare_kernel(const float* __rest
   const float hf = bf16lo(h2);
   hi[i] = (uint16_t)h2;
   lo[i] = (uint16_t)(pack_bf16(v - hf, 0.f) & 0xFFFFu);
+}
+
+// Blocks of a weight-gradient launch: whole rounds of one 32-tile super-tile per XCD.
+static long long wgrad_blocks(int Et, int n_p_tiles, int n_q_tiles) {
+  const long long n_super = (long long)Et * ((n_p_tiles + 7) / 8) * ((n_q_tiles + 3) / 4);
+  return (n_super + kNumXcd - 1) / kNumXcd * kNumXcd * 32;
 }
 
 template <int KIND, bool P_RC, bool Q_RC, int NQ, int NPASS, int EPI>
@@ -680,8 +697,9 @@ extern "C" int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_pe
   A.sched = sched; A.max_tiles = max_tiles; A.offsets = offsets; A.Et = D.Et; A.accumulate = accumulate ? 1 : 0;
   A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
   A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
+  // (also with no rows at all: the weight gradients read the expert order from the schedule)
+  MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles);
   if (D.N > 0) {
-    MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles);
     // dH = dY Wd^T, then dG, dU and H from the saved G, U
     A.n_q_tiles = (D.f + TILE - 1) / TILE; A.q_dim = D.f; A.k_dim = D.d;
     A.p0 = dy_perm; A.p_ld = D.d;
@@ -700,13 +718,13 @@ extern "C" int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_pe
   A.p0 = h; A.p1 = nullptr; A.p_ld = D.f;
   A.q0 = dy_perm; A.q1 = nullptr; A.q_ld = D.d;
   A.f0 = dw_down; A.f1 = nullptr; A.f_expert_stride = (size_t)D.f * D.d; A.c_ld = D.d;
-  MOE_TRY((launch_gemm<1, true, true, 1, 1, EPI_F32>("ffn_bwd_dw_down", A, (long long)D.Et * ((A.n_p_tiles + 7) / 8) * ((A.n_q_tiles + 3) / 4) * 32, st)));
+  MOE_TRY((launch_gemm<1, true, true, 1, 1, EPI_F32>("ffn_bwd_dw_down", A, wgrad_blocks(D.Et, A.n_p_tiles, A.n_q_tiles), st)));
   // dWg[e], dWu[e] = X_e^T dG_e, X_e^T dU_e   (rows d, columns f)
   A.p_dim = D.d; A.n_p_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.f; A.n_q_tiles = (D.f + 127) / 128;
   A.p0 = x_perm; A.p_ld = D.d;
   A.q0 = dg; A.q1 = du; A.q_ld = D.f;
   A.f0 = dw_gate; A.f1 = dw_up; A.f_expert_stride = (size_t)D.d * D.f; A.c_ld = D.f;
-  MOE_TRY((launch_gemm<1, true, true, 2, 1, EPI_F32>("ffn_bwd_dw_gate_up", A, (long long)D.Et * ((A.n_p_tiles + 7) / 8) * ((A.n_q_tiles + 3) / 4) * 32, st)));
+  MOE_TRY((launch_gemm<1, true, true, 2, 1, EPI_F32>("ffn_bwd_dw_gate_up", A, wgrad_blocks(D.Et, A.n_p_tiles, A.n_q_tiles), st)));
   return launch_status();
 }
 
