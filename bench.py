@@ -100,6 +100,24 @@ def run_layer_bench(moe, W, args):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # forward and backward on their own (HIP events on the launch stream, median and minimum over single steps)
+    def per_step_ms(fn, n):
+        out = []
+        for _ in range(n):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            out.append(e0.elapsed_time(e1))
+        out.sort()
+        return {"median_ms": round(out[len(out) // 2], 4), "min_ms": round(out[0], 4)}
+    n_split = max(3, min(args.steps, 10))
+    split = {"fwd": per_step_ms(lambda: moe.layer_forward(buf, x, wg, wu, wd, logits), n_split),
+             "bwd": per_step_ms(lambda: moe.layer_backward(buf, dout, wg, wu, wd, accumulate=False,
+                                                           with_router=logits is not None), n_split),
+             "fwd_bwd": per_step_ms(step, n_split)}
+
     # instrumented pass: per-launch HIP events on the launch stream
     moe.profile_reset()
     moe.profile_enable(True)
@@ -114,7 +132,7 @@ def run_layer_bench(moe, W, args):
     for name, ms in recs:
         per_kernel.setdefault(name, []).append(ms)
     kernels = {k: {"launches_per_step": len(v) // prof_steps, "avg_ms": sum(v) / len(v)} for k, v in per_kernel.items()}
-    return inp, sh, elapsed, kernels, gen_s
+    return inp, sh, elapsed, kernels, gen_s, split
 
 
 def run_streaming_bench(moe, W, steps):
@@ -305,7 +323,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
-    inp, sh, elapsed, kernels, gen_s = run_layer_bench(moe, W, args)
+    inp, sh, elapsed, kernels, gen_s, split = run_layer_bench(moe, W, args)
     flops = sh.flops_fwd_bwd()
     ms_per_step = elapsed / args.steps * 1e3
     tflops = flops / (ms_per_step * 1e-3) / 1e12
@@ -343,6 +361,7 @@ def main():
                    "flops_per_step": flops},
         "frac_bf16_mfma_peak": round(tflops / PEAK_BF16_MFMA_TFLOPS, 4),
         "roofline": roofline,
+        "phases": split,
         "kernels": kern_out,
     }
     if not args.no_streaming:

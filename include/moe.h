@@ -141,7 +141,9 @@ int moe_permute_bwd_add(const moe_shape* shape, const uint16_t* dx_perm, const i
  *   x_perm [N,d] bf16 in;  offsets [E'+1] int32 in (device; never read by the host)
  *   w_gate, w_up [E',d,f] bf16 in;  w_down [E',f,d] bf16 in
  *   y_perm [N,d] bf16 out;  save_g, save_u [N,f] bf16 out (the activations backward needs; together with
- *   x_perm this is the 3*d_ffn + d_model values per row of the paper's activation-memory model)
+ *   x_perm this is the 3*d_ffn + d_model values per row of the paper's activation-memory model).  save_g and
+ *   save_u may be NULL together: G and U then live in the workspace only (checkpointed forward, to be followed by
+ *   moe_grouped_ffn_bwd_recompute)
  * Experts with no rows cost nothing and touch nothing. */
 int moe_grouped_ffn_fwd(const moe_shape* shape, const uint16_t* x_perm, const int32_t* offsets,
                         const uint16_t* w_gate, const uint16_t* w_up, const uint16_t* w_down,
@@ -160,6 +162,15 @@ int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_perm, const u
                         const uint16_t* w_down, const uint16_t* save_g, const uint16_t* save_u,
                         uint16_t* dx_perm, float* dw_gate, float* dw_up, float* dw_down, int accumulate,
                         void* ws, size_t ws_bytes, void* stream);
+
+/* The same backward without saved activations (the selective activation checkpointing of the paper's evaluation,
+ * Section V; the "fused kernel" row of the activation-memory model of Section III-A drops to d_model values per
+ * row): G and U are recomputed from x_perm with the forward's own kernel (4*d*f extra FLOP per row, bit-identical
+ * to what forward produced), then everything is as in moe_grouped_ffn_bwd. */
+int moe_grouped_ffn_bwd_recompute(const moe_shape* shape, const uint16_t* dy_perm, const uint16_t* x_perm,
+                                  const int32_t* offsets, const uint16_t* w_gate, const uint16_t* w_up,
+                                  const uint16_t* w_down, uint16_t* dx_perm, float* dw_gate, float* dw_up,
+                                  float* dw_down, int accumulate, void* ws, size_t ws_bytes, void* stream);
 
 /* Local unpack + weighted combine (the per-GPU half of the combine of Section III-B):
  *   out[t] = sum_{j<K'} topk_w[t,j] * y_perm[row_of_slot[t*K'+j]]   (fp32 accumulate in slot order, one bf16

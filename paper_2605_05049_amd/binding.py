@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = (
     "moe_status_str", "moe_workspace_bytes", "moe_abi_version",
     "moe_profile_enable", "moe_profile_count", "moe_profile_get", "moe_profile_reset",
     "moe_route_topk", "moe_route_topk_bwd", "moe_permute", "moe_permute_bwd", "moe_permute_bwd_add",
-    "moe_router_fwd", "moe_router_bwd", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_unpermute_combine_bwd",
+    "moe_router_fwd", "moe_router_bwd", "moe_grouped_ffn_bwd_recompute", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_unpermute_combine_bwd",
 )
 
 
@@ -88,6 +88,7 @@ def load_library():
         "moe_router_bwd": [sp, V, V, V, V, V, c_int, V, c_size_t, V],
         "moe_grouped_ffn_fwd": [sp, V, V, V, V, V, V, V, V, V, c_size_t, V],
         "moe_grouped_ffn_bwd": [sp, V, V, V, V, V, V, V, V, V, V, V, V, c_int, V, c_size_t, V],
+        "moe_grouped_ffn_bwd_recompute": [sp, V, V, V, V, V, V, V, V, V, V, c_int, V, c_size_t, V],
         "moe_unpermute_combine": [sp, V, V, V, V, V],
         "moe_unpermute_combine_bwd": [sp, V, V, V, V, V, V, V],
     }
@@ -258,10 +259,27 @@ def moe_grouped_ffn_fwd(shape, x_perm, offsets, w_gate, w_up, w_down, y_perm, sa
     rc = load_library().moe_grouped_ffn_fwd(
         ctypes.byref(s._c), _ptr(x_perm, bf, s.N * s.d_model, "x_perm"), _ptr(offsets, torch.int32, s.E_total + 1, "offsets"),
         _ptr(w_gate, bf, nw, "w_gate"), _ptr(w_up, bf, nw, "w_up"), _ptr(w_down, bf, nw, "w_down"),
-        _ptr(y_perm, bf, s.N * s.d_model, "y_perm"), _ptr(save_g, bf, s.N * s.d_ffn, "save_g"),
-        _ptr(save_u, bf, s.N * s.d_ffn, "save_u"), _ptr(ws, None, None, "ws"), ws.numel() * ws.element_size(),
-        _stream(stream))
+        _ptr(y_perm, bf, s.N * s.d_model, "y_perm"),
+        None if save_g is None else _ptr(save_g, bf, s.N * s.d_ffn, "save_g"),
+        None if save_u is None else _ptr(save_u, bf, s.N * s.d_ffn, "save_u"), _ptr(ws, None, None, "ws"),
+        ws.numel() * ws.element_size(), _stream(stream))
     _check("moe_grouped_ffn_fwd", rc)
+
+
+def moe_grouped_ffn_bwd_recompute(shape, dy_perm, x_perm, offsets, w_gate, w_up, w_down, dx_perm, dw_gate, dw_up, dw_down,
+                                  accumulate, ws, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    nw = s.E_total * s.d_model * s.d_ffn
+    rc = load_library().moe_grouped_ffn_bwd_recompute(
+        ctypes.byref(s._c), _ptr(dy_perm, bf, s.N * s.d_model, "dy_perm"), _ptr(x_perm, bf, s.N * s.d_model, "x_perm"),
+        _ptr(offsets, torch.int32, s.E_total + 1, "offsets"), _ptr(w_gate, bf, nw, "w_gate"), _ptr(w_up, bf, nw, "w_up"),
+        _ptr(w_down, bf, nw, "w_down"), _ptr(dx_perm, bf, s.N * s.d_model, "dx_perm"),
+        _ptr(dw_gate, torch.float32, nw, "dw_gate"), _ptr(dw_up, torch.float32, nw, "dw_up"),
+        _ptr(dw_down, torch.float32, nw, "dw_down"), int(bool(accumulate)), _ptr(ws, None, None, "ws"),
+        ws.numel() * ws.element_size(), _stream(stream))
+    _check("moe_grouped_ffn_bwd_recompute", rc)
 
 
 def moe_grouped_ffn_bwd(shape, dy_perm, x_perm, offsets, w_gate, w_up, w_down, save_g, save_u, dx_perm,

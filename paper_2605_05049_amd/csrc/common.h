@@ -53,6 +53,7 @@ struct WsLayout {
   size_t splitk_counters;   // kSplitCounters int32: arrivals per split tile
   size_t splitk_partial;    // kSplitParts fp32 tiles of 256 x 256: partial sums of the tiles whose K range is split
   size_t h, dg, du, nf_bytes;
+  size_t g_re, u_re;        // [N,f] bf16: G, U when the caller does not keep them (checkpointed forward, recomputing backward)
   size_t router_offsets;    // 8 int32: {0, T} and {0, E}, the one-segment "offsets" of the router's GEMMs
   size_t dl_hi, dl_lo;      // [T, Epad] bf16: head and remainder of the fp32 dlogits (Epad = E rounded up to 64)
   size_t total;
@@ -83,6 +84,8 @@ inline WsLayout ws_layout(const Dims& D) {
   L.h = off; off += L.nf_bytes;
   L.dg = off; off += L.nf_bytes;
   L.du = off; off += L.nf_bytes;
+  L.g_re = off; off += L.nf_bytes;
+  L.u_re = off; off += L.nf_bytes;
   L.router_offsets = off; off += 256;
   const size_t dl_bytes = round_up((size_t)D.T * round_up((size_t)D.E, 64) * sizeof(uint16_t) + 256, 256);
   L.dl_hi = off; off += dl_bytes;

@@ -633,12 +633,17 @@ extern "C" int moe_grouped_ffn_fwd(const moe_shape* shape, const uint16_t* x_per
   int rc = common_checks(shape, &D, ws, ws_bytes, &L);
   if (rc != MOE_OK) return rc;
   MOE_REQUIRE_PTR(x_perm); MOE_REQUIRE_PTR(offsets); MOE_REQUIRE_PTR(w_gate); MOE_REQUIRE_PTR(w_up); MOE_REQUIRE_PTR(w_down);
-  MOE_REQUIRE_PTR(y_perm); MOE_REQUIRE_PTR(save_g); MOE_REQUIRE_PTR(save_u);
+  MOE_REQUIRE_PTR(y_perm);
+  if ((save_g == nullptr) != (save_u == nullptr)) return MOE_ERR_NULL;  // kept together or not at all
   MOE_REQUIRE_ALIGNED(x_perm); MOE_REQUIRE_ALIGNED(offsets); MOE_REQUIRE_ALIGNED(w_gate); MOE_REQUIRE_ALIGNED(w_up);
   MOE_REQUIRE_ALIGNED(w_down); MOE_REQUIRE_ALIGNED(y_perm); MOE_REQUIRE_ALIGNED(save_g); MOE_REQUIRE_ALIGNED(save_u);
   if (D.N == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
   char* wsb = static_cast<char*>(ws);
+  if (save_g == nullptr) {  // checkpointed forward: G and U go to the workspace and are not kept
+    save_g = reinterpret_cast<uint16_t*>(wsb + L.g_re);
+    save_u = reinterpret_cast<uint16_t*>(wsb + L.u_re);
+  }
   int32_t* sched = reinterpret_cast<int32_t*>(wsb + L.sched);
   uint32_t* zero_page = reinterpret_cast<uint32_t*>(wsb + L.zero_page);
   int32_t* counters = reinterpret_cast<int32_t*>(wsb + L.splitk_counters);
@@ -810,4 +815,46 @@ extern "C" int moe_router_bwd(const moe_shape* shape, const uint16_t* x, const u
   const long long e_tiles = (D.E + TILE - 1) / TILE;
   MOE_TRY((launch_gemm<0, true, true, 1, 2, EPI_F32>("router_bwd_dw", A, e_tiles * A.n_q_tiles, st)));
   return launch_status();
+}
+
+extern "C" int moe_grouped_ffn_bwd_recompute(const moe_shape* shape, const uint16_t* dy_perm, const uint16_t* x_perm,
+                                             const int32_t* offsets, const uint16_t* w_gate, const uint16_t* w_up,
+                                             const uint16_t* w_down, uint16_t* dx_perm, float* dw_gate, float* dw_up,
+                                             float* dw_down, int accumulate, void* ws, size_t ws_bytes, void* stream) {
+  using namespace moe;
+  Dims D;
+  WsLayout L;
+  int rc = common_checks(shape, &D, ws, ws_bytes, &L);
+  if (rc != MOE_OK) return rc;
+  // every argument is checked before the first launch (the call below checks them again)
+  MOE_REQUIRE_PTR(dy_perm); MOE_REQUIRE_PTR(x_perm); MOE_REQUIRE_PTR(offsets); MOE_REQUIRE_PTR(w_gate); MOE_REQUIRE_PTR(w_up);
+  MOE_REQUIRE_PTR(w_down); MOE_REQUIRE_PTR(dx_perm); MOE_REQUIRE_PTR(dw_gate); MOE_REQUIRE_PTR(dw_up); MOE_REQUIRE_PTR(dw_down);
+  MOE_REQUIRE_ALIGNED(dy_perm); MOE_REQUIRE_ALIGNED(x_perm); MOE_REQUIRE_ALIGNED(offsets); MOE_REQUIRE_ALIGNED(w_gate);
+  MOE_REQUIRE_ALIGNED(w_up); MOE_REQUIRE_ALIGNED(w_down); MOE_REQUIRE_ALIGNED(dx_perm); MOE_REQUIRE_ALIGNED(dw_gate);
+  MOE_REQUIRE_ALIGNED(dw_up); MOE_REQUIRE_ALIGNED(dw_down);
+  char* wsb = static_cast<char*>(ws);
+  uint16_t* g_re = reinterpret_cast<uint16_t*>(wsb + L.g_re);
+  uint16_t* u_re = reinterpret_cast<uint16_t*>(wsb + L.u_re);
+  if (D.N > 0) {
+    // G, U = X Wg, X Wu once more (the same kernel as in forward, hence the same bits); its H output is overwritten
+    // by the backward's own
+    hipStream_t st = (hipStream_t)stream;
+    int32_t* sched = reinterpret_cast<int32_t*>(wsb + L.sched);
+    uint32_t* zero_page = reinterpret_cast<uint32_t*>(wsb + L.zero_page);
+    int32_t* counters = reinterpret_cast<int32_t*>(wsb + L.splitk_counters);
+    const int max_tiles = (int)sched_max_tiles(D);
+    const long long ub_tiles = D.N / TILE + D.Et;
+    MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles);
+    GemmArgs A = {};
+    A.sched = sched; A.max_tiles = max_tiles; A.offsets = offsets; A.Et = D.Et;
+    A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
+    A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
+    A.n_q_tiles = (D.f + 127) / 128; A.q_dim = D.f; A.k_dim = D.d;
+    A.p0 = x_perm; A.p_ld = D.d;
+    A.q0 = w_gate; A.q1 = w_up; A.q_ld = D.f; A.q_expert_stride = (size_t)D.d * D.f;
+    A.c0 = g_re; A.c1 = u_re; A.c2 = reinterpret_cast<uint16_t*>(wsb + L.h); A.c_ld = D.f;
+    MOE_TRY((launch_gemm<0, false, true, 2, 1, EPI_SWIGLU>("ffn_bwd_recompute_gate_up", A, ub_tiles * A.n_q_tiles, st)));
+  }
+  return moe_grouped_ffn_bwd(shape, dy_perm, x_perm, offsets, w_gate, w_up, w_down, g_re, u_re, dx_perm, dw_gate, dw_up, dw_down,
+                             accumulate, ws, ws_bytes, stream);
 }

@@ -79,6 +79,10 @@ def test_argument_checks_run_before_any_launch(lib):
                                    FAKE, 1 << 40, None) == -1
     assert lib.moe_grouped_ffn_bwd(sp, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0,
                                    FAKE, 16, None) == -4
+    assert lib.moe_grouped_ffn_fwd(sp, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, 1 << 40, None) == -1   # G without U
+    assert lib.moe_grouped_ffn_bwd_recompute(sp, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 16, None) == -4
+    assert lib.moe_grouped_ffn_bwd_recompute(sp, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 1 << 40, None) == -1
+    assert lib.moe_grouped_ffn_bwd_recompute(sp, None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 1 << 40, None) == -1
     assert lib.moe_unpermute_combine(sp, FAKE, FAKE, None, FAKE, None) == -1
     assert lib.moe_unpermute_combine(sp, FAKE, FAKE, ODD, FAKE, None) == -3
     assert lib.moe_unpermute_combine_bwd(sp, FAKE, FAKE, FAKE, FAKE, FAKE, None, None) == -1

@@ -383,3 +383,36 @@ def test_dense_reduction_on_gpu(moe):
     sh = W.MoEShape(200, 128, 192, 1, 1)
     inp = W.random_layer_inputs(sh, seed=3)
     check_layer_against_definition(moe, inp)
+
+
+def test_recomputing_backward_is_bit_identical(moe):
+    """Checkpointed forward (G, U not kept) + recomputing backward against the saving pair: same kernels on the same
+    inputs, so every output must match bit for bit (parity with the oracle then follows from the tests above)."""
+    wl = W.scaled_down(W.WORKLOADS["finegrained"])
+    sh = wl.shape
+    inp = W.make_layer_inputs(wl, seed=5)
+    s = moe.Shape.of(sh)
+    idx, w, _ = O.route_topk(inp["logits"], sh.k, sh.E_shared, True)
+    counts, offsets, ros, sor = O.permute_maps(idx, sh.E_total)
+    x_perm = dev_bf16(O.permute_rows(inp["x"], sor, sh.K_slots))
+    dy = dev_bf16(W.f32_to_bf16_bits(np.random.default_rng(9).standard_normal((sh.N, sh.d_model)).astype(np.float32)))
+    wg, wu, wd = dev_bf16(inp["w_gate"]), dev_bf16(inp["w_up"]), dev_bf16(inp["w_down"])
+    off = dev(offsets.astype(np.int32))
+    ws = ws_for(moe, s)
+    e = lambda *sz, dtype=torch.bfloat16: torch.empty(*sz, dtype=dtype, device="cuda")  # noqa: E731
+    y1, y2, sg, su = e(sh.N, sh.d_model), e(sh.N, sh.d_model), e(sh.N, sh.d_ffn), e(sh.N, sh.d_ffn)
+    moe.moe_grouped_ffn_fwd(s, x_perm, off, wg, wu, wd, y1, sg, su, ws)
+    moe.moe_grouped_ffn_fwd(s, x_perm, off, wg, wu, wd, y2, None, None, ws)
+    assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+    outs = []
+    for mode in ("saved", "recompute"):
+        dx = e(sh.N, sh.d_model)
+        dws = [e(sh.E_total, sh.d_model, sh.d_ffn, dtype=torch.float32), e(sh.E_total, sh.d_model, sh.d_ffn, dtype=torch.float32),
+               e(sh.E_total, sh.d_ffn, sh.d_model, dtype=torch.float32)]
+        if mode == "saved":
+            moe.moe_grouped_ffn_bwd(s, dy, x_perm, off, wg, wu, wd, sg, su, dx, dws[0], dws[1], dws[2], 0, ws)
+        else:
+            moe.moe_grouped_ffn_bwd_recompute(s, dy, x_perm, off, wg, wu, wd, dx, dws[0], dws[1], dws[2], 0, ws)
+        outs.append([dx.view(torch.int16)] + [t.view(torch.int32) for t in dws])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
