@@ -185,6 +185,27 @@ int moe_unpermute_combine_bwd(const moe_shape* shape, const uint16_t* dout, cons
                               const int32_t* row_of_slot, const float* topk_w, uint16_t* dy_perm,
                               float* dtopk_w, void* stream);
 
+/* ---- Load balancing through expert migration (Section VI).  Host functions on host arrays; nothing here touches
+ * the GPU.  A placement is `groups[n_groups][n_experts / n_groups]`: the expert ids hosted by each GPU of an
+ * expert-parallel group, every expert exactly once (else MOE_ERR_SHAPE). */
+
+/* Running per-expert token counts (the load history an external scheduler inspects between steps):
+ * running[e] += counts[e], counts being a host copy of what moe_permute wrote. */
+int moe_load_accumulate(int64_t* running, const int32_t* counts, int n_experts);
+
+/* ratio = max_k s_k / mean_k s_k with s_k the summed load of group k (1 = balanced): the quantity an external
+ * scheduler compares with its threshold before it asks for a rebalancing. */
+int moe_load_imbalance(const int64_t* load, int n_experts, int n_groups, const int32_t* groups, double* ratio);
+
+/* Hill-climbing swap-based minimal rebalancing (Algorithm 2).  Up to max_iters times (the paper uses 100): take the
+ * group with the largest summed load and the one with the smallest (first one on ties); among all exchanges of one
+ * expert of the former with one of the latter take the one that reduces the difference of the two sums the most
+ * (first one on ties; it must reduce it), exchange the two experts in place, and stop when none does.
+ *   load [n_experts] int64 in (>= 0);  groups in/out;  n_swaps out;  swaps [2*max_iters] int32 out, may be NULL:
+ *   the pairs (expert that left the heavy group, expert that left the light group) in the order performed. */
+int moe_rebalance_experts(const int64_t* load, int n_experts, int n_groups, int32_t* groups, int max_iters,
+                          int32_t* n_swaps, int32_t* swaps);
+
 #ifdef __cplusplus
 }
 #endif

@@ -643,3 +643,50 @@ def elementwise_excess(got, ref, scale, rtol):
     if ref.size == 0:
         return 0.0
     return float((np.abs(got - ref) - rtol * (np.abs(ref) + np.asarray(scale, dtype=F64))).max())
+
+
+# --------------------------------------------------------------------------------------------------------------
+# load balancing through expert migration (Section VI): load statistics and the hill-climbing swap rebalancer
+# --------------------------------------------------------------------------------------------------------------
+def group_loads(load, groups):
+    """s_k = sum of the loads of the experts in group k; `groups` is a list of lists of expert ids."""
+    return [int(sum(int(load[e]) for e in g)) for g in groups]
+
+
+def load_imbalance(load, groups):
+    """max_k s_k / mean_k s_k (1.0 = perfectly balanced; 1.0 as well when nothing was routed at all)."""
+    s = group_loads(load, groups)
+    tot = sum(s)
+    return 1.0 if tot == 0 else max(s) * len(s) / tot
+
+
+def rebalance_hill_climbing(load, groups, max_iters=100):
+    """Hill-climbing swap-based minimal rebalancing (Section VI, Algorithm 2), in the paper's notation.
+
+    Each iteration takes the group with the largest sum (k+) and the one with the smallest (k-); among all swaps of
+    one expert of k+ with one of k- it takes the one that shrinks |s_{k+} - s_{k-}| the most (it must shrink it), and
+    stops when no swap does.  Readings where the listing is silent: arg max / arg min and the best swap keep the
+    first candidate on ties (groups and their members are scanned in stored order), and a swap exchanges the two
+    experts in place (each takes the other's position).  Returns (groups, swaps) with swaps = [(expert from k+,
+    expert from k-), ...] in the order performed; the input is not modified."""
+    G = [list(g) for g in groups]
+    swaps = []
+    for _ in range(max_iters):
+        s = group_loads(load, G)
+        k_plus = max(range(len(G)), key=lambda k: (s[k], -k))
+        k_minus = min(range(len(G)), key=lambda k: (s[k], k))
+        delta = s[k_plus] - s[k_minus]
+        best, best_gain = None, 0
+        for i, e1 in enumerate(G[k_plus]):
+            n1 = int(load[e1])
+            for j, e2 in enumerate(G[k_minus]):
+                n2 = int(load[e2])
+                d2 = abs((s[k_plus] - n1 + n2) - (s[k_minus] - n2 + n1))
+                if d2 < delta and (delta - d2) > best_gain:
+                    best_gain, best = delta - d2, (i, j)
+        if best is None:
+            break
+        i, j = best
+        swaps.append((G[k_plus][i], G[k_minus][j]))
+        G[k_plus][i], G[k_minus][j] = G[k_minus][j], G[k_plus][i]
+    return G, swaps

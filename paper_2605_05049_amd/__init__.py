@@ -9,6 +9,6 @@ from .binding import (  # noqa: F401
     moe_route_topk, moe_route_topk_bwd, moe_permute, moe_permute_bwd, moe_permute_bwd_add, moe_router_fwd,
     moe_router_bwd, moe_grouped_ffn_bwd_recompute, moe_grouped_ffn_fwd,
     moe_grouped_ffn_bwd, moe_unpermute_combine, moe_unpermute_combine_bwd, EXPORTED_SYMBOLS,
-    profile_enable, profile_reset, profile_records,
+    profile_enable, profile_reset, profile_records, load_accumulate, load_imbalance, rebalance_experts,
 )
 from .layer import MoeLayerBuffers, layer_forward, layer_backward  # noqa: F401

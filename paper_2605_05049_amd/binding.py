@@ -92,6 +92,9 @@ def load_library():
         "moe_unpermute_combine": [sp, V, V, V, V, V],
         "moe_unpermute_combine_bwd": [sp, V, V, V, V, V, V, V],
     }
+    sigs["moe_load_accumulate"] = [V, V, c_int]
+    sigs["moe_load_imbalance"] = [V, c_int, c_int, V, POINTER(ctypes.c_double)]
+    sigs["moe_rebalance_experts"] = [V, c_int, c_int, V, c_int, POINTER(ctypes.c_int32), V]
     for name, args in sigs.items():
         fn = getattr(lib, name)
         fn.restype = c_int
@@ -317,3 +320,42 @@ def moe_unpermute_combine_bwd(shape, dout, y_perm, row_of_slot, topk_w, dy_perm,
         _ptr(row_of_slot, torch.int32, s.N, "row_of_slot"), _ptr(topk_w, torch.float32, s.N, "topk_w"),
         _ptr(dy_perm, bf, s.N * s.d_model, "dy_perm"), _ptr(dtopk_w, torch.float32, s.N, "dtopk_w"), _stream(stream))
     _check("moe_unpermute_combine_bwd", rc)
+
+
+# ---- host-side load statistics and rebalancing (NumPy arrays; nothing here touches the GPU) ------------------
+
+def _np(a, dtype, what):
+    import numpy as np
+    if not isinstance(a, np.ndarray) or a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise ValueError(f"{what}: expected a C-contiguous numpy array of {np.dtype(dtype).name}")
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def load_accumulate(running, counts):
+    """running[e] += counts[e] in place (running int64 [E], counts int32 [E], both on the host)."""
+    import numpy as np
+    if running.shape != counts.shape:
+        raise ValueError("running and counts differ in shape")
+    _check("moe_load_accumulate", load_library().moe_load_accumulate(_np(running, np.int64, "running"), _np(counts, np.int32, "counts"),
+                                                                     int(running.size)))
+
+
+def load_imbalance(load, groups) -> float:
+    """max group load / mean group load for a placement `groups` (int32 [n_groups, experts per group])."""
+    import numpy as np
+    r = ctypes.c_double(0.0)
+    _check("moe_load_imbalance", load_library().moe_load_imbalance(_np(load, np.int64, "load"), int(load.size), int(groups.shape[0]),
+                                                                   _np(groups, np.int32, "groups"), ctypes.byref(r)))
+    return float(r.value)
+
+
+def rebalance_experts(load, groups, max_iters=100):
+    """Algorithm 2 on a copy of `groups`; returns (new groups, swaps) with swaps an int32 [n, 2] array."""
+    import numpy as np
+    out = np.ascontiguousarray(groups, dtype=np.int32).copy()
+    swaps = np.zeros((max(int(max_iters), 1), 2), dtype=np.int32)
+    n = ctypes.c_int32(0)
+    _check("moe_rebalance_experts", load_library().moe_rebalance_experts(
+        _np(load, np.int64, "load"), int(load.size), int(out.shape[0]), _np(out, np.int32, "groups"), int(max_iters),
+        ctypes.byref(n), _np(swaps, np.int32, "swaps")))
+    return out, swaps[:n.value].copy()

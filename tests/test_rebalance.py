@@ -1,0 +1,142 @@
+"""Load statistics and the hill-climbing swap rebalancer (Section VI, Algorithm 2): pins of the oracle, then the
+library's host implementation against the oracle, bit for bit (integers; no GPU involved)."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import paper_2605_05049_amd as moe
+from oracle import moe_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "rebalance_small.txt")
+
+
+def read_golden():
+    rec = {}
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, rest = line.split(" ", 1)
+        rec[key] = [[int(v) for v in part.split()] for part in rest.split("|")]
+    return rec
+
+
+# ---- oracle pins ------------------------------------------------------------------------------------------------
+
+def test_oracle_reproduces_the_hand_worked_example():
+    g = read_golden()
+    load = g["load"][0]
+    out, swaps = O.rebalance_hill_climbing(load, g["groups_in"])
+    assert out == g["groups_out"]
+    assert [list(s) for s in swaps] == g["swaps"]
+    assert O.group_loads(load, out) == g["sums_out"][0]
+    assert O.group_loads(load, g["groups_in"]) == [170, 40, 113]
+    assert abs(O.load_imbalance(load, g["groups_in"]) - 170 * 3 / 323) < 1e-15
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_oracle_invariants(seed):
+    rng = np.random.default_rng(seed)
+    K, m = int(rng.integers(2, 6)), int(rng.integers(1, 6))
+    load = rng.integers(0, 1000, size=K * m)
+    if seed % 3 == 0:
+        load[rng.integers(0, K * m, size=K)] *= 20           # a few hot experts
+    groups = rng.permutation(K * m).reshape(K, m).tolist()
+    prev = [list(g) for g in groups]
+    cur, swaps = O.rebalance_hill_climbing(load, groups, max_iters=100)
+    assert groups == prev                                       # the input is not modified
+    assert sorted(e for g in cur for e in g) == list(range(K * m)) and all(len(g) == m for g in cur)
+    # replay the swaps one by one: each takes one expert of the heaviest and one of the lightest group, strictly
+    # shrinks their difference, never raises the maximum and never lowers the minimum
+    state = [list(g) for g in groups]
+    for e1, e2 in swaps:
+        s = O.group_loads(load, state)
+        k1 = next(k for k, g in enumerate(state) if e1 in g)
+        k2 = next(k for k, g in enumerate(state) if e2 in g)
+        assert s[k1] == max(s) and s[k2] == min(s)
+        i, j = state[k1].index(e1), state[k2].index(e2)
+        state[k1][i], state[k2][j] = e2, e1
+        s2 = O.group_loads(load, state)
+        assert abs(s2[k1] - s2[k2]) < s[k1] - s[k2]
+        assert max(s2) <= max(s) and min(s2) >= min(s)
+    assert state == cur
+    # at the end no exchange between the heaviest and the lightest group improves their difference (local optimum)
+    if len(swaps) < 100:
+        s = O.group_loads(load, cur)
+        kp, km = s.index(max(s)), s.index(min(s))
+        d = s[kp] - s[km]
+        for e1, e2 in itertools.product(cur[kp], cur[km]):
+            x = int(load[e1]) - int(load[e2])
+            assert not abs(d - 2 * x) < d
+    assert O.load_imbalance(load, cur) <= O.load_imbalance(load, groups) + 1e-12
+
+
+def test_oracle_special_cases():
+    # already balanced, a single group, all-zero load: nothing to do
+    assert O.rebalance_hill_climbing([5, 5, 5, 5], [[0, 1], [2, 3]])[1] == []
+    assert O.rebalance_hill_climbing([9, 1, 4], [[0, 1, 2]])[1] == []
+    assert O.rebalance_hill_climbing([0, 0, 0, 0], [[0, 1], [2, 3]])[1] == []
+    assert O.load_imbalance([0, 0], [[0], [1]]) == 1.0
+    # two groups of one expert: swapping only mirrors the difference, so it is never an improvement
+    assert O.rebalance_hill_climbing([7, 3], [[0], [1]])[1] == []
+    # the iteration cap is honoured
+    load = [100, 90, 80, 70, 1, 2, 3, 4]
+    full = O.rebalance_hill_climbing(load, [[0, 1, 2, 3], [4, 5, 6, 7]])[1]
+    assert len(full) >= 2 and O.rebalance_hill_climbing(load, [[0, 1, 2, 3], [4, 5, 6, 7]], max_iters=1)[1] == full[:1]
+    # two groups, brute force over all placements: with two experts per group the first swap already reaches the optimum
+    load = [10, 1, 2, 8]
+    best = min(abs(sum(load[e] for e in c) - sum(load[e] for e in range(4) if e not in c)) for c in itertools.combinations(range(4), 2))
+    out, _ = O.rebalance_hill_climbing(load, [[0, 3], [1, 2]])
+    s = O.group_loads(load, out)
+    assert abs(s[0] - s[1]) == best
+
+
+# ---- the library's host implementation against the oracle ----------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(12))
+def test_library_matches_oracle(seed):
+    moe.load_library()
+    rng = np.random.default_rng(100 + seed)
+    K, m = int(rng.integers(1, 9)), int(rng.integers(1, 33))
+    load = rng.integers(0, 5000, size=K * m).astype(np.int64)
+    if seed % 2:
+        load[rng.integers(0, K * m, size=max(1, K * m // 10))] *= 30
+    if seed == 4:
+        load[:] = 7                                              # every sum ties
+    groups = rng.permutation(K * m).astype(np.int32).reshape(K, m)
+    iters = 100 if seed % 4 else 3
+    ref_groups, ref_swaps = O.rebalance_hill_climbing(load, groups.tolist(), max_iters=iters)
+    got_groups, got_swaps = moe.rebalance_experts(load, groups, max_iters=iters)
+    assert got_groups.tolist() == ref_groups
+    assert got_swaps.tolist() == [list(s) for s in ref_swaps]
+    assert abs(moe.load_imbalance(load, got_groups) - O.load_imbalance(load, ref_groups)) < 1e-12
+
+
+def test_library_golden_and_statistics():
+    g = read_golden()
+    load = np.array(g["load"][0], dtype=np.int64)
+    out, swaps = moe.rebalance_experts(load, np.array(g["groups_in"], dtype=np.int32))
+    assert out.tolist() == g["groups_out"] and swaps.tolist() == g["swaps"]
+    running = np.zeros(12, dtype=np.int64)
+    for step in range(3):
+        moe.load_accumulate(running, (np.arange(12, dtype=np.int32) * (step + 1)))
+    assert running.tolist() == (np.arange(12) * 6).tolist()
+
+
+def test_library_rejects_bad_placements():
+    import ctypes
+    lib = moe.load_library()
+    load = np.arange(6, dtype=np.int64)
+    n = ctypes.c_int32(0)
+    bad = np.array([0, 1, 2, 3, 4, 4], dtype=np.int32)         # expert 4 twice, expert 5 missing
+    p = lambda a: a.ctypes.data_as(ctypes.c_void_p)            # noqa: E731
+    assert lib.moe_rebalance_experts(p(load), 6, 2, p(bad), 100, ctypes.byref(n), None) == -2
+    ok = np.arange(6, dtype=np.int32)
+    assert lib.moe_rebalance_experts(p(load), 6, 4, p(ok), 100, ctypes.byref(n), None) == -2    # 6 experts in 4 groups
+    assert lib.moe_rebalance_experts(None, 6, 2, p(ok), 100, ctypes.byref(n), None) == -1
+    assert lib.moe_rebalance_experts(p(load), 6, 2, p(ok), 100, None, None) == -1
+    neg = load.copy(); neg[2] = -1
+    assert lib.moe_rebalance_experts(p(neg), 6, 2, p(ok), 100, ctypes.byref(n), None) == -2
+    assert lib.moe_rebalance_experts(p(load), 6, 2, p(ok), 100, ctypes.byref(n), None) == 0 and ok.tolist() != list(range(6))
