@@ -14,7 +14,9 @@ EXPORTED_SYMBOLS = (
     "moe_status_str", "moe_workspace_bytes", "moe_abi_version",
     "moe_profile_enable", "moe_profile_count", "moe_profile_get", "moe_profile_reset",
     "moe_route_topk", "moe_route_topk_bwd", "moe_permute", "moe_permute_bwd", "moe_permute_bwd_add",
-    "moe_router_fwd", "moe_router_bwd", "moe_grouped_ffn_bwd_recompute", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_unpermute_combine", "moe_unpermute_combine_bwd",
+    "moe_router_fwd", "moe_router_bwd", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_grouped_ffn_bwd_recompute",
+    "moe_unpermute_combine", "moe_unpermute_combine_bwd",
+    "moe_load_accumulate", "moe_load_imbalance", "moe_rebalance_experts",
 )
 
 
