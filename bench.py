@@ -260,6 +260,41 @@ def run_router_bench(moe, W, workload, steps):
     return out
 
 
+def run_halo_bench(moe, steps):
+    """The three single-GPU steps of the hierarchical all-to-all on an 8-node x 8-rank layout with 8 MiB per
+    destination (512 MiB send buffer: larger than the last-level cache), two rotating buffer sets."""
+    import torch
+    nodes, R, row = 8, 8, 8 << 20
+    M = nodes - 1
+    sets = []
+    for _ in range(2):
+        sets.append(dict(S=torch.empty(nodes * R * row, dtype=torch.uint8, device="cuda").random_(0, 255),
+                         F2=torch.empty(M * R * row, dtype=torch.uint8, device="cuda").random_(0, 255),
+                         F3=torch.empty(M * R * row, dtype=torch.uint8, device="cuda"),
+                         P1=torch.empty(R * row, dtype=torch.uint8, device="cuda").random_(0, 255),
+                         O=torch.empty(nodes * R * row, dtype=torch.uint8, device="cuda")))
+    calls = {"halo_pack_remote": (lambda b: moe.moe_halo_pack_remote(b["S"], b["F3"], nodes, R, 3), 2 * M * R * row),
+             "halo_repack": (lambda b: moe.moe_halo_repack(b["F2"], b["F3"], M, R), 2 * M * R * row),
+             "halo_unpack": (lambda b: moe.moe_halo_unpack(b["P1"], b["F2"], b["O"], nodes, R, 3), 2 * nodes * R * row)}
+    out = {"layout": "8 nodes x 8 ranks, 8 MiB per destination", "peak_GBs": PEAK_HBM_GBS, "kernels": {}}
+    for name, (fn, nbytes) in calls.items():
+        for i in range(2):
+            fn(sets[i])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            fn(sets[i % 2])
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        out["kernels"][name] = {"avg_us": round(ms * 1e3, 1), "algorithmic_MB": round(nbytes / 1e6, 1),
+                                "GBs": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    del sets
+    torch.cuda.empty_cache()
+    return out
+
+
 def run_copy_calibration():
     """A plain device-to-device copy of known size (512 MiB read + 512 MiB written per launch, 5 launches): the yard
     stick the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by."""
@@ -368,6 +403,8 @@ def main():
         res["permute_combine"] = run_streaming_bench(moe, W, steps=20)
     if not args.no_streaming and args.workload != "shard":
         res["router"] = run_router_bench(moe, W, args.workload, steps=20)
+    if not args.no_streaming and args.workload == "mixtral":
+        res["halo_pack"] = run_halo_bench(moe, steps=10)
     if args.copy_calibration:
         res["copy_calibration"] = run_copy_calibration()
     if not args.no_cpu_baseline:

@@ -185,6 +185,23 @@ int moe_unpermute_combine_bwd(const moe_shape* shape, const uint16_t* dout, cons
                               const int32_t* row_of_slot, const float* topk_w, uint16_t* dy_perm,
                               float* dtopk_w, void* stream);
 
+/* ---- The single-GPU steps of the hierarchical all-to-all (Section V, Algorithm 1).  One rank's send buffer S has
+ * N = num_nodes * R rows (R ranks per node) of row_bytes bytes (a multiple of 16; any element type): row n*R + l goes
+ * to local rank l of node n.  M = num_nodes - 1; "the i-th remote node" counts the nodes other than node_id in
+ * increasing order.  All pointers are device pointers, 16-byte aligned; the exchanges between ranks are the caller's. */
+
+/* Phase 2 pack: F2s[i*R + r] = S[n_i*R + r] for every remote node n_i.   S [N rows] in;  F2s [M*R rows] out. */
+int moe_halo_pack_remote(const void* S, void* F2s, int num_nodes, int R, size_t row_bytes, int node_id, void* stream);
+
+/* Phase 3 repack: the received [M, R, row] buffer becomes [R, M, row]: F3s[r*M + i] = F2r[i*R + r], so that row block
+ * r holds everything the remote nodes sent for local rank r.   F2r [M*R rows] in;  F3s [R*M rows] out. */
+int moe_halo_repack(const void* F2r, void* F3s, int M, int R, size_t row_bytes, void* stream);
+
+/* Final placement: O[node_id*R + r] = P1[r] (phase 1 result) and O[n_i*R + p] = F3r[p*M + i] (phase 3 result).
+ *   P1 [R rows] in;  F3r [R*M rows] in (may be NULL when num_nodes == 1);  O [N rows] out. */
+int moe_halo_unpack(const void* P1, const void* F3r, void* O, int num_nodes, int R, size_t row_bytes, int node_id,
+                    void* stream);
+
 /* ---- Load balancing through expert migration (Section VI).  Host functions on host arrays; nothing here touches
  * the GPU.  A placement is `groups[n_groups][n_experts / n_groups]`: the expert ids hosted by each GPU of an
  * expert-parallel group, every expert exactly once (else MOE_ERR_SHAPE). */

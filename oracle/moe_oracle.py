@@ -690,3 +690,88 @@ def rebalance_hill_climbing(load, groups, max_iters=100):
         swaps.append((G[k_plus][i], G[k_minus][j]))
         G[k_plus][i], G[k_minus][j] = G[k_minus][j], G[k_plus][i]
     return G, swaps
+
+
+# --------------------------------------------------------------------------------------------------------------
+# the local (single-GPU) steps of the hierarchical all-to-all (Section V, Algorithm 1)
+#
+# One rank holds a send buffer S [N, D] with N = num_nodes * R rows (R = ranks per node): row n*R + l goes to local
+# rank l of node n.  The algorithm's own steps that touch only this rank's memory are written out below in its
+# notation; the exchanges between ranks are not part of this library (halo_all_to_all_reference simulates them
+# on the host only to pin the local steps against the definition of an all-to-all).
+# --------------------------------------------------------------------------------------------------------------
+def halo_remote_nodes(num_nodes, node_id):
+    """N_- : the other nodes, in increasing order."""
+    return [n for n in range(num_nodes) if n != node_id]
+
+
+def halo_pack_remote(S, num_nodes, R, node_id):
+    """Phase 2 pack: F2s = IndexSelect(S, idx) with idx = [n R, ..., n R + R - 1 | n in N_-]; shape [M R, D]."""
+    S = np.asarray(S)
+    idx = [n * R + r for n in halo_remote_nodes(num_nodes, node_id) for r in range(R)]
+    return S[idx]
+
+
+def halo_repack_phase3(F2r, M, R):
+    """Phase 3 repack: view F2r as (M, R, D), permute to (R, M, D), flatten to [R, M D]: row l = everything the
+    remote nodes sent for local rank l."""
+    F2r = np.asarray(F2r)
+    D = F2r.shape[1]
+    return np.ascontiguousarray(F2r.reshape(M, R, D).transpose(1, 0, 2)).reshape(R, M * D)
+
+
+def halo_unpack_output(P1, F3r, num_nodes, R, node_id):
+    """Final placement: O[local_start : local_start + R] = P1; T = permute(view(F3r, R, M, D), [1,0,2]);
+    O[n R : (n+1) R] = T[i] for the i-th remote node n."""
+    P1, F3r = np.asarray(P1), np.asarray(F3r)
+    D = P1.shape[1]
+    rem = halo_remote_nodes(num_nodes, node_id)
+    M = len(rem)
+    O = np.empty((num_nodes * R, D), dtype=P1.dtype)
+    O[node_id * R:(node_id + 1) * R] = P1
+    Tm = F3r.reshape(R, M, D).transpose(1, 0, 2)
+    for i, n in enumerate(rem):
+        O[n * R:(n + 1) * R] = Tm[i]
+    return O
+
+
+def halo_all_to_all_reference(send, num_nodes, R):
+    """The whole three-phase algorithm over all num_nodes*R ranks with the exchanges done by plain host indexing:
+    `send[g]` is rank g's S [N, D].  Returns the list of every rank's output O.  (Used only by the pins: the result
+    must be the all-to-all, O_g[j] = S_j[g].)"""
+    W = num_nodes * R
+    rank = lambda n, l: n * R + l  # noqa: E731
+    out = []
+    P1 = [None] * W
+    F2s = [None] * W
+    for g in range(W):
+        n, l = divmod(g, R)
+        F2s[g] = halo_pack_remote(send[g], num_nodes, R, n)
+    for g in range(W):
+        n, l = divmod(g, R)
+        # phase 1: intra-node all-to-all of the node's own R rows: rank l receives row l of every local peer's block
+        P1[g] = np.stack([np.asarray(send[rank(n, p)])[n * R + l] for p in range(R)])
+    F3r = [None] * W
+    F3s = [None] * W
+    for g in range(W):
+        n, l = divmod(g, R)
+        rem = halo_remote_nodes(num_nodes, n)
+        # phase 2: slice i of the receive buffer comes from the same local rank of the i-th remote node, which sends
+        # the slice it packed for this node
+        parts = []
+        for src_node in rem:
+            peer = rank(src_node, l)
+            i_at_peer = halo_remote_nodes(num_nodes, src_node).index(n)
+            parts.append(F2s[peer][i_at_peer * R:(i_at_peer + 1) * R])
+        F3s[g] = halo_repack_phase3(np.concatenate(parts), len(rem), R) if rem else None
+    for g in range(W):
+        n, l = divmod(g, R)
+        M = num_nodes - 1
+        if M:
+            D = np.asarray(send[g]).shape[1]
+            # phase 3: intra-node all-to-all of the [R, M D] buffers: rank l receives row l of every local peer
+            F3r[g] = np.stack([F3s[rank(n, p)][l] for p in range(R)])
+        else:
+            F3r[g] = np.empty((R, 0), dtype=np.asarray(send[g]).dtype)
+        out.append(halo_unpack_output(P1[g], F3r[g], num_nodes, R, n))
+    return out

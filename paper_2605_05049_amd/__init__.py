@@ -10,5 +10,6 @@ from .binding import (  # noqa: F401
     moe_router_bwd, moe_grouped_ffn_bwd_recompute, moe_grouped_ffn_fwd,
     moe_grouped_ffn_bwd, moe_unpermute_combine, moe_unpermute_combine_bwd, EXPORTED_SYMBOLS,
     profile_enable, profile_reset, profile_records, load_accumulate, load_imbalance, rebalance_experts,
+    moe_halo_pack_remote, moe_halo_repack, moe_halo_unpack,
 )
 from .layer import MoeLayerBuffers, layer_forward, layer_backward  # noqa: F401

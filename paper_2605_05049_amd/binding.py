@@ -17,6 +17,7 @@ EXPORTED_SYMBOLS = (
     "moe_router_fwd", "moe_router_bwd", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_grouped_ffn_bwd_recompute",
     "moe_unpermute_combine", "moe_unpermute_combine_bwd",
     "moe_load_accumulate", "moe_load_imbalance", "moe_rebalance_experts",
+    "moe_halo_pack_remote", "moe_halo_repack", "moe_halo_unpack",
 )
 
 
@@ -94,6 +95,9 @@ def load_library():
         "moe_unpermute_combine": [sp, V, V, V, V, V],
         "moe_unpermute_combine_bwd": [sp, V, V, V, V, V, V, V],
     }
+    sigs["moe_halo_pack_remote"] = [V, V, c_int, c_int, c_size_t, c_int, V]
+    sigs["moe_halo_repack"] = [V, V, c_int, c_int, c_size_t, V]
+    sigs["moe_halo_unpack"] = [V, V, V, c_int, c_int, c_size_t, c_int, V]
     sigs["moe_load_accumulate"] = [V, V, c_int]
     sigs["moe_load_imbalance"] = [V, c_int, c_int, V, POINTER(ctypes.c_double)]
     sigs["moe_rebalance_experts"] = [V, c_int, c_int, V, c_int, POINTER(ctypes.c_int32), V]
@@ -322,6 +326,48 @@ def moe_unpermute_combine_bwd(shape, dout, y_perm, row_of_slot, topk_w, dy_perm,
         _ptr(row_of_slot, torch.int32, s.N, "row_of_slot"), _ptr(topk_w, torch.float32, s.N, "topk_w"),
         _ptr(dy_perm, bf, s.N * s.d_model, "dy_perm"), _ptr(dtopk_w, torch.float32, s.N, "dtopk_w"), _stream(stream))
     _check("moe_unpermute_combine_bwd", rc)
+
+
+# ---- single-GPU steps of the hierarchical all-to-all (device tensors; rows of any dtype, 16-byte multiples) -----
+
+def _rows(t, n_rows, what):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{what}: expected a contiguous CUDA tensor")
+    nbytes = t.numel() * t.element_size()
+    if n_rows == 0:
+        return ctypes.c_void_p(t.data_ptr()), 0
+    if nbytes % n_rows:
+        raise ValueError(f"{what}: {nbytes} bytes do not split into {n_rows} rows")
+    return ctypes.c_void_p(t.data_ptr()), nbytes // n_rows
+
+
+def moe_halo_pack_remote(S, F2s, num_nodes, R, node_id, stream=None):
+    ps, rb = _rows(S, num_nodes * R, "S")
+    pd, rb2 = _rows(F2s, (num_nodes - 1) * R, "F2s")
+    if num_nodes > 1 and rb != rb2:
+        raise ValueError("S and F2s differ in row size")
+    _check("moe_halo_pack_remote", load_library().moe_halo_pack_remote(ps, pd, int(num_nodes), int(R), rb, int(node_id), _stream(stream)))
+
+
+def moe_halo_repack(F2r, F3s, M, R, stream=None):
+    ps, rb = _rows(F2r, M * R, "F2r")
+    pd, rb2 = _rows(F3s, M * R, "F3s")
+    if rb != rb2:
+        raise ValueError("F2r and F3s differ in size")
+    _check("moe_halo_repack", load_library().moe_halo_repack(ps, pd, int(M), int(R), rb if M else 16, _stream(stream)))
+
+
+def moe_halo_unpack(P1, F3r, O, num_nodes, R, node_id, stream=None):
+    p1, rb = _rows(P1, R, "P1")
+    po, rb2 = _rows(O, num_nodes * R, "O")
+    if rb != rb2:
+        raise ValueError("P1 and O differ in row size")
+    p3 = None
+    if num_nodes > 1:
+        p3, rb3 = _rows(F3r, R * (num_nodes - 1), "F3r")
+        if rb3 != rb:
+            raise ValueError("F3r and O differ in row size")
+    _check("moe_halo_unpack", load_library().moe_halo_unpack(p1, p3, po, int(num_nodes), int(R), rb, int(node_id), _stream(stream)))
 
 
 # ---- host-side load statistics and rebalancing (NumPy arrays; nothing here touches the GPU) ------------------
