@@ -239,6 +239,9 @@ FFN_CASES = [
     (256, 512, 1024, 8, 2, 0, 0),      # the tiny workload's shape
     (700, 128, 256, 3, 1, 1, 0),       # ~230 rows per expert + a 700-row shared expert: several row tiles, ragged
     (90, 256, 128, 16, 2, 0, 5),       # experts with a handful of rows
+    (600, 256, 2048, 2, 1, 0, 0),      # few tiles and a long K in Y = H W_down and dX: the last-round tiles are split along K
+    (513, 64, 64, 1, 1, 0, 0),         # one expert, the smallest legal widths, a one-row third tile
+    (40, 128, 192, 24, 1, 0, 20),      # most experts empty: zero-filled weight gradients, experts ordered by row count
 ]
 
 
@@ -416,3 +419,20 @@ def test_recomputing_backward_is_bit_identical(moe):
         outs.append([dx.view(torch.int16)] + [t.view(torch.int32) for t in dws])
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+def test_grouped_ffn_with_no_rows(moe):
+    """T = 0: nothing to compute, but overwritten weight gradients must be exact zeros and accumulated ones untouched."""
+    shape = W.MoEShape(0, 128, 64, 4, 2)
+    s = moe.Shape.of(shape)
+    ws = ws_for(moe, s)
+    off = torch.zeros(5, dtype=torch.int32, device="cuda")
+    z = torch.zeros((16,), dtype=torch.bfloat16, device="cuda")
+    wts = [torch.randn(4, 128, 64, device="cuda").to(torch.bfloat16), torch.randn(4, 128, 64, device="cuda").to(torch.bfloat16),
+           torch.randn(4, 64, 128, device="cuda").to(torch.bfloat16)]
+    dws = [torch.full((4, 128, 64), 3.0, device="cuda"), torch.full((4, 128, 64), 3.0, device="cuda"), torch.full((4, 64, 128), 3.0, device="cuda")]
+    moe.moe_grouped_ffn_fwd(s, z, off, wts[0], wts[1], wts[2], z, z, z, ws)
+    moe.moe_grouped_ffn_bwd(s, z, z, off, wts[0], wts[1], wts[2], z, z, z, dws[0], dws[1], dws[2], 1, ws)
+    assert all(bool((t == 3.0).all()) for t in dws)
+    moe.moe_grouped_ffn_bwd(s, z, z, off, wts[0], wts[1], wts[2], z, z, z, dws[0], dws[1], dws[2], 0, ws)
+    assert all(not bool(t.any()) for t in dws)
