@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E, published
 # HBM-side bytes per launch (read + written) of the grouped GEMM kernels on the mixtral workload, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/grouped_gemm_mixtral_hbm_traffic.txt (scaled by the plain-copy
 # calibration of the same runs).  Counters cannot be read from inside this script; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {"mixtral": {"ffn_bwd_dx": 4388266873, "ffn_bwd_dw_gate_up": 6836230102, "ffn_fwd_gate_up_swiglu": 5477393544, "ffn_fwd_down": 1962078093, "ffn_bwd_dw_down": 3292636251, "ffn_bwd_dh_dswiglu": 3358667747}}
+MEASURED_TRAFFIC_BYTES = {"mixtral": {"ffn_bwd_dx": 4204784003, "ffn_bwd_dw_gate_up": 6577029793, "ffn_fwd_gate_up_swiglu": 5243373641, "ffn_fwd_down": 1948759247, "ffn_bwd_dw_down": 3289359749, "ffn_bwd_dh_dswiglu": 3402838715}}
 
 
 def parse_args():
