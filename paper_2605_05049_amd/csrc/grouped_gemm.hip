@@ -221,8 +221,8 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     if (SPLITK) {
       const int rem = (int)(cnt % kCusPerXcd);
       const int nk_all = ((A.k_dim + BK - 1) / BK) * NPASS;
-      if (rem > 0 && rem <= kCusPerXcd / 2 && nk_all >= 32) {
-        split = min(min(kCusPerXcd / rem, 8), nk_all / 16);
+      if (rem > 0 && rem <= kCusPerXcd / 2 && nk_all >= 16) {
+        split = min(min(kCusPerXcd / rem, 8), nk_all / 8);
         full = cnt - rem;
       }
     }
@@ -403,32 +403,40 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
       __builtin_amdgcn_s_waitcnt(0xC07F);
       __builtin_amdgcn_wave_barrier();
     }
+    // All parts of a tile carry the same blockIdx.x % 8 and so run on one XCD, whose L2 they share: a store that has
+    // been acknowledged (vmcnt) is then visible to the other parts, and no cache has to be written back or
+    // invalidated.  That placement is checked, not assumed: a part that finds itself on another XCD falls back to
+    // device-wide fences and says so in the upper half of the counter, which makes the reducing part fence as well.
     __shared__ int arrived_before;
-    __threadfence();   // this thread's part of the partial tile is visible device-wide ...
-    __syncthreads();   // ... and so is every other thread's, before the arrival is counted
-    if (tid == 0) arrived_before = atomicAdd(A.counters + (part_slot / kCusPerXcd) * (kCusPerXcd / 2) + (part_slot % kCusPerXcd) / split, 1);
+    const bool on_home_xcd = (__builtin_amdgcn_s_getreg((31 << 11) | 20) & 0xF) == (unsigned)(blockIdx.x % kNumXcd);
+    if (on_home_xcd) __builtin_amdgcn_s_waitcnt(0x0F70);  // this thread's part of the partial tile has reached the L2
+    else __threadfence();
+    __syncthreads();   // ... and so has every other thread's, before the arrival is counted
+    if (tid == 0)
+      arrived_before = atomicAdd(A.counters + (part_slot / kCusPerXcd) * (kCusPerXcd / 2) + (part_slot % kCusPerXcd) / split,
+                                 on_home_xcd ? 1 : 0x10001);
     __syncthreads();
-    if (arrived_before != split - 1) return;
-    __threadfence();   // the other parts' partial tiles, written before their arrivals, are visible to this block
+    if ((arrived_before & 0xFFFF) != split - 1) return;
+    if (!on_home_xcd || (arrived_before >> 16)) __threadfence();  // some part wrote through another XCD's L2
     const float* parts = A.partial + (size_t)(part_slot - part) * (TILE * TILE);
-#pragma unroll 1
-    for (int it = 0; it < (TILE * TILE / 8) / NTHREADS; it++) {
-      const int idx = it * NTHREADS + tid;
-      const int p = idx >> 5, q = (idx & 31) * 8;
-      if (p < p_valid && q < q_valid) {
-        float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int sp = 0; sp < split; sp++) {
-          const float4 x0 = *reinterpret_cast<const float4*>(parts + (size_t)sp * (TILE * TILE) + p * TILE + q);
-          const float4 x1 = *reinterpret_cast<const float4*>(parts + (size_t)sp * (TILE * TILE) + p * TILE + q + 4);
-          x[0] += x0.x; x[1] += x0.y; x[2] += x0.z; x[3] += x0.w; x[4] += x1.x; x[5] += x1.y; x[6] += x1.z; x[7] += x1.w;
-        }
-        if (EPI == EPI_F32) {
-          float* dst = A.f0 + (size_t)expert * A.f_expert_stride + (size_t)(p_row0 + p) * A.c_ld + q0_col + q;
-          for (int i = 0; i < 8 && q + i < q_valid; i++) dst[i] = A.accumulate ? dst[i] + x[i] : x[i];
-        } else {
-          *reinterpret_cast<uint4*>(A.c0 + (size_t)(p_row0 + p) * A.c_ld + q0_col + q) =
-              make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
-        }
+    // the valid part of the tile only: p_valid rows of ceil(q_valid / 8) groups of 8 columns, spread over all threads
+    const int nqv = (q_valid + 7) >> 3;
+    const int n_items = p_valid * nqv;
+#pragma unroll 2
+    for (int idx = tid; idx < n_items; idx += NTHREADS) {
+      const int p = idx / nqv, q = (idx - p * nqv) * 8;
+      float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int sp = 0; sp < split; sp++) {
+        const float4 x0 = *reinterpret_cast<const float4*>(parts + (size_t)sp * (TILE * TILE) + p * TILE + q);
+        const float4 x1 = *reinterpret_cast<const float4*>(parts + (size_t)sp * (TILE * TILE) + p * TILE + q + 4);
+        x[0] += x0.x; x[1] += x0.y; x[2] += x0.z; x[3] += x0.w; x[4] += x1.x; x[5] += x1.y; x[6] += x1.z; x[7] += x1.w;
+      }
+      if (EPI == EPI_F32) {
+        float* dst = A.f0 + (size_t)expert * A.f_expert_stride + (size_t)(p_row0 + p) * A.c_ld + q0_col + q;
+        for (int i = 0; i < 8 && q + i < q_valid; i++) dst[i] = A.accumulate ? dst[i] + x[i] : x[i];
+      } else {
+        *reinterpret_cast<uint4*>(A.c0 + (size_t)(p_row0 + p) * A.c_ld + q0_col + q) =
+            make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
       }
     }
     return;
