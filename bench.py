@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E, published
 # HBM-side bytes per launch (read + written) of the grouped GEMM kernels on the mixtral workload, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/grouped_gemm_mixtral_hbm_traffic.txt (scaled by the plain-copy
 # calibration of the same runs).  Counters cannot be read from inside this script; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {"mixtral": {"ffn_bwd_dx": 4204784003, "ffn_bwd_dw_gate_up": 6577029793, "ffn_fwd_gate_up_swiglu": 5243373641, "ffn_fwd_down": 1948759247, "ffn_bwd_dw_down": 3289359749, "ffn_bwd_dh_dswiglu": 3402838715}}
+MEASURED_TRAFFIC_BYTES = {"mixtral": {"ffn_bwd_dx": 3854146862, "ffn_bwd_dw_gate_up": 6577116271, "ffn_fwd_gate_up_swiglu": 4658355365, "ffn_fwd_down": 1942290528, "ffn_bwd_dw_down": 3289370786, "ffn_bwd_dh_dswiglu": 3220287860}}
 
 
 def parse_args():

@@ -209,6 +209,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   constexpr bool SPLITK = (KIND == 0 && (EPI == EPI_BF16 || EPI == EPI_F32));
   constexpr bool NARROW = (KIND == 0 && EPI == EPI_F32);  // fp32-output row-tile problems are the router's: E rows or columns
   int split = 1, part = 0, part_slot = 0;
+  int p_tile_idx;  // index of the tile along p
   if (KIND == 0) {
     const int n_row_tiles = A.sched[0];
     const long long total = (long long)n_row_tiles * A.n_q_tiles;
@@ -247,6 +248,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     const int mt = (int)(local % e_tiles);
     p_row0 = e_lo + mt * TILE;
     p_valid = min(TILE, e_hi - p_row0);
+    p_tile_idx = mt;
     q0_col = qt * TQ;
     k_len = A.k_dim;
   } else {
@@ -267,6 +269,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     const int pt = (super % sp) * 8 + (in_super & 7);
     const int qt = (super / sp) * 4 + (in_super >> 3);
     if (pt >= A.n_p_tiles || qt >= A.n_q_tiles) return;  // padding of the super-tile grid
+    p_tile_idx = pt;
     const int e_lo = A.offsets[expert], e_hi = A.offsets[expert + 1];
     k_len = e_hi - e_lo;
     krow0 = (size_t)e_lo;
@@ -313,11 +316,19 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     Q.ld = A.q_ld;
     Q.r_valid = q_valid;
   }
+  // Tiles that are neighbours along p share their q panel and run side by side on one XCD, in step with each other.
+  // In every other one of them each wavefront issues the q loads of the wavefront that loads at the other time of
+  // the step (any wavefront may issue any instruction of a stage: the LDS destination comes with the instruction).
+  // Each half of the shared panel is then requested right after the barrier by half of its users, and the requests
+  // the other half makes half a step later find it in, or on its way to, the L2.  (Left out where it measured
+  // slower or was not measured: the forward down projection and the router's skinny problems.)
+  constexpr bool ALTERNATE_Q = !NARROW && !(KIND == 0 && Q_RC && NQ == 1 && EPI == EPI_BF16);
+  const int iwq = ALTERNATE_Q ? (wave ^ ((p_tile_idx & 1) << 2)) : wave;
   unsigned pvo[4], qvo[4];
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     pvo[i] = load_offset<P_RC, false>(P, wave * 4 + i, lane);
-    qvo[i] = load_offset<Q_RC, NQ == 2>(Q, wave * 4 + i, lane);
+    qvo[i] = load_offset<Q_RC, NQ == 2>(Q, iwq * 4 + i, lane);
   }
   const int nk_pass = (k_len + BK - 1) / BK;  // k-steps per K pass
   const int nk = nk_pass * NPASS;             // k-steps of the whole contraction
@@ -326,7 +337,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     const bool second = (NPASS == 2) && j >= nk_pass;
     const int k0 = (second ? j - nk_pass : j) * BK;
     issue_tile<P_RC, false, NARROW>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage, wave, lane);
-    issue_tile<Q_RC, NQ == 2, NARROW>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + OPERAND_BYTES, wave, lane);
+    issue_tile<Q_RC, NQ == 2, NARROW>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + OPERAND_BYTES, iwq, lane);
   };
   // the k-steps this block multiplies: all of them, or its part of a split tile
   const int kt_per = (nk + split - 1) / split;
