@@ -260,6 +260,38 @@ def run_router_bench(moe, W, workload, steps):
     return out
 
 
+def run_graph_bench(moe, W, steps):
+    """The launch-bound end of the range: the tiny workload's whole step (about 20 kernels) issued call by call and
+    replayed as one captured HIP graph."""
+    import torch
+    wl = W.WORKLOADS["tiny"]
+    inp = W.make_layer_inputs(wl, seed=0)
+    s = moe.Shape.of(wl.shape)
+    x, dout = dev_bf16(inp["x"]), dev_bf16(inp["dout"])
+    wg, wu, wd = dev_bf16(inp["w_gate"]), dev_bf16(inp["w_up"]), dev_bf16(inp["w_down"])
+    logits = torch.from_numpy(inp["logits"]).cuda()
+    buf = moe.MoeLayerBuffers(s)
+
+    def eager():
+        moe.layer_forward(buf, x, wg, wu, wd, logits)
+        moe.layer_backward(buf, dout, wg, wu, wd)
+
+    step = moe.CapturedLayerStep(buf, x, dout, wg, wu, wd, logits=logits)
+    out = {"workload": wl.name}
+    for label, fn in (("eager_ms", eager), ("graph_ms", step.replay)):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[label] = round(e0.elapsed_time(e1) / steps, 4)
+    return out
+
+
 def run_halo_bench(moe, steps):
     """The three single-GPU steps of the hierarchical all-to-all on an 8-node x 8-rank layout with 8 MiB per
     destination (512 MiB send buffer: larger than the last-level cache), two rotating buffer sets."""
@@ -405,6 +437,7 @@ def main():
         res["router"] = run_router_bench(moe, W, args.workload, steps=20)
     if not args.no_streaming and args.workload == "mixtral":
         res["halo_pack"] = run_halo_bench(moe, steps=10)
+        res["graph_replay"] = run_graph_bench(moe, W, steps=200)
     if args.copy_calibration:
         res["copy_calibration"] = run_copy_calibration()
     if not args.no_cpu_baseline:

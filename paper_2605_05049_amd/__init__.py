@@ -12,4 +12,4 @@ from .binding import (  # noqa: F401
     profile_enable, profile_reset, profile_records, load_accumulate, load_imbalance, rebalance_experts,
     moe_halo_pack_remote, moe_halo_repack, moe_halo_unpack,
 )
-from .layer import MoeLayerBuffers, layer_forward, layer_backward  # noqa: F401
+from .layer import MoeLayerBuffers, CapturedLayerStep, layer_forward, layer_backward  # noqa: F401

@@ -82,3 +82,37 @@ def layer_backward(buf: MoeLayerBuffers, dout, w_gate, w_up, w_down, accumulate=
     B.moe_permute_bwd(s, buf.dx_perm, buf.row_of_slot, buf.dx, stream)
     if with_router and buf.dlogits is not None:
         B.moe_route_topk_bwd(s, buf.dtopk_w, buf.topk_idx, buf.topk_w, buf.probs, buf.dlogits, stream)
+
+
+class CapturedLayerStep:
+    """One forward+backward of a layer recorded into a HIP graph and replayed with a single launch.
+
+    Every node of the graph is one of the library's kernels: the entry points allocate nothing, never synchronise
+    the host, take the ragged counts from device memory and clear their own counters with kernels (no memset
+    nodes), so a whole step can be captured.  torch.cuda.CUDAGraph drives the capture.  The tensors passed in are the
+    graph's static inputs: refill them in place (`x.copy_(...)`) and call `replay()`; results land in `buf` as
+    after `layer_forward` + `layer_backward`."""
+
+    def __init__(self, buf: MoeLayerBuffers, x, dout, w_gate, w_up, w_down, logits=None, w_router=None,
+                 accumulate=False, with_router=True, warmup=2):
+        import torch
+        self.buf = buf
+        self._args = (x, dout, w_gate, w_up, w_down, logits, w_router, accumulate, with_router)
+        side = torch.cuda.Stream()  # default priority
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(warmup):
+                self._step()
+        torch.cuda.current_stream().wait_stream(side)
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self._step()
+
+    def _step(self):
+        x, dout, w_gate, w_up, w_down, logits, w_router, accumulate, with_router = self._args
+        layer_forward(self.buf, x, w_gate, w_up, w_down, logits=logits, w_router=w_router)
+        layer_backward(self.buf, dout, w_gate, w_up, w_down, accumulate=accumulate, with_router=with_router,
+                       x=x if w_router is not None else None, w_router=w_router)
+
+    def replay(self):
+        self.graph.replay()
