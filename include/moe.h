@@ -2,8 +2,7 @@
  * moe.h -- C ABI of the MI355X (gfx950) MoE expert layer: one GPU's share of a Mixture-of-Experts layer,
  * forward and backward.
  *
- * The layer is the one the paper names in Section II-A (expert FFNs, each receiving only the tokens routed to
- * it by a learned gating function) with the symbols of its notation table (Section III-A: d = d_model,
+ * The layer is the top-k gated set of expert FFNs of Section II-A, with the symbols of the paper's notation table (Section III-A: d = d_model,
  * E routed experts, E_s shared always-active experts, top-k routing, n_mat = 3 SwiGLU matrices, expert FFN
  * dimension d_ffn) and the weight shapes of its memory model (Section III-A: W_up, W_gate in R^{d x d_ffn},
  * W_down in R^{d_ffn x d}).  The flow is the per-layer flow of Section IV with the two all-to-alls removed
@@ -24,7 +23,8 @@
  *   - Outputs are fully overwritten, except the weight gradients when `accumulate` is 1.
  *
  * Shape limits:  1 <= k <= E <= 1024,  E' <= 1024,  T >= 0 (T = 0 is a no-op returning MOE_OK),
- * T*K' < 2^31,  d_model and d_ffn positive multiples of 64.
+ * T*K' < 2^31,  d_model and d_ffn positive multiples of 64 and at most 2^22 (the kernels address a tile's rows
+ * with 32-bit byte offsets: 256 rows of a 2^22-element bf16 row pitch still fit).
  */
 #ifndef MOE_H_
 #define MOE_H_
@@ -163,9 +163,9 @@ int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_perm, const u
                         uint16_t* dx_perm, float* dw_gate, float* dw_up, float* dw_down, int accumulate,
                         void* ws, size_t ws_bytes, void* stream);
 
-/* The same backward without saved activations (the selective activation checkpointing of the paper's evaluation,
- * Section V; the "fused kernel" row of the activation-memory model of Section III-A drops to d_model values per
- * row): G and U are recomputed from x_perm with the forward's own kernel (4*d*f extra FLOP per row, bit-identical
+/* The same backward without saved activations (the selective activation checkpointing used for the full-model
+ * training runs of Section VII-B; in the activation-memory model of Section III-A the layer's share then drops to
+ * d_model values per row): G and U are recomputed from x_perm with the forward's own kernel (4*d*f extra FLOP per row, bit-identical
  * to what forward produced), then everything is as in moe_grouped_ffn_bwd. */
 int moe_grouped_ffn_bwd_recompute(const moe_shape* shape, const uint16_t* dy_perm, const uint16_t* x_perm,
                                   const int32_t* offsets, const uint16_t* w_gate, const uint16_t* w_up,
@@ -214,7 +214,7 @@ int moe_load_accumulate(int64_t* running, const int32_t* counts, int n_experts);
  * scheduler compares with its threshold before it asks for a rebalancing. */
 int moe_load_imbalance(const int64_t* load, int n_experts, int n_groups, const int32_t* groups, double* ratio);
 
-/* Hill-climbing swap-based minimal rebalancing (Algorithm 2).  Up to max_iters times (the paper uses 100): take the
+/* The swap rebalancer of Section VI, Algorithm 2.  Up to max_iters times (the paper uses 100): take the
  * group with the largest summed load and the one with the smallest (first one on ties); among all exchanges of one
  * expert of the former with one of the latter take the one that reduces the difference of the two sums the most
  * (first one on ties; it must reduce it), exchange the two experts in place, and stop when none does.

@@ -4,8 +4,8 @@ Only the tests, the smoke check and the benchmark's cpu_baseline leg may import 
 with the HIP path and never calls it.  Everything is NumPy float64; `@` (matmul), `argsort(kind="stable")`
 and `bincount` are the only library primitives used as steps.
 
-What it computes is the plain definition of the layer the paper names (Section II-A: expert FFNs, each
-receiving only the tokens routed to it by a learned gating function; notation table in Section III-A: E routed
+What it computes is the plain definition of the layer the paper names (Section II-A: top-k gated expert FFNs;
+notation table in Section III-A: E routed
 experts, E_s shared always-active experts, top-k routing, n_mat = 3 SwiGLU matrices; Section III-A memory
 model: W_up, W_gate in R^{d x f}, W_down in R^{f x d}, per-expert token sets s_e; Section III-B: dispatch
 moves b*s*k rows of d_model values, combine is the reverse).  The paper gives no formula beyond that, so the
@@ -102,10 +102,23 @@ def route_topk(logits, k, E_shared=0, renorm=True):
     z = np.asarray(logits, dtype=F64)
     T, E = z.shape
     assert 1 <= k <= E
-    probs = softmax_rows(z)
     # stable sort of -logit keeps the original (ascending id) order among equal logits
     order = np.argsort(-z, axis=1, kind="stable")
-    sel = order[:, :k]
+    return gate_of_selection(z, order[:, :k], E_shared, renorm)
+
+
+def gate_of_selection(logits, sel, E_shared=0, renorm=True):
+    """The continuous part of the gate for a GIVEN choice sel [T,k] of routed experts per token: probs = softmax over
+    all E logits, weight of slot j = probs[sel_j], divided by the sum over the k chosen ones when `renorm`; shared
+    slots appended with ids E.. and weight 1.  route_topk is this function applied to its own choice; a test may
+    apply it to another valid choice (the choice is piecewise constant in the logits, so near a tie two choices
+    are equally right and everything downstream is defined by the one taken).
+    Returns (topk_idx [T,K'] int32, topk_w [T,K'] float64, probs [T,E] float64)."""
+    z = np.asarray(logits, dtype=F64)
+    T, E = z.shape
+    sel = np.asarray(sel).astype(np.int64)
+    k = sel.shape[1]
+    probs = softmax_rows(z)
     w = np.take_along_axis(probs, sel, axis=1)
     if renorm:
         w = w / w.sum(axis=1, keepdims=True)
@@ -661,7 +674,7 @@ def load_imbalance(load, groups):
 
 
 def rebalance_hill_climbing(load, groups, max_iters=100):
-    """Hill-climbing swap-based minimal rebalancing (Section VI, Algorithm 2), in the paper's notation.
+    """The swap rebalancer of Section VI, Algorithm 2.
 
     Each iteration takes the group with the largest sum (k+) and the one with the smallest (k-); among all swaps of
     one expert of k+ with one of k- it takes the one that shrinks |s_{k+} - s_{k-}| the most (it must shrink it), and

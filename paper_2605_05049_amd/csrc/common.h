@@ -14,6 +14,7 @@ constexpr int kMaxExperts = 1024;    // E' limit of the ABI
 constexpr int kPermSlotsPerBlock = 1024;  // slots ranked by one block of the counting sort
 constexpr int kSplitParts = 256;     // K-split parts in flight at most: 32 per XCD (one per CU)
 constexpr int kSplitCounters = 128;  // split tiles at most: 16 per XCD
+constexpr int kMaxWidth = 1 << 22;   // d_model, d_ffn limit: 256 rows x 2^22 elements x 2 bytes < 2^32
 constexpr int kMinTileRows = 32;     // smallest row-tile height any GEMM schedule may use
 
 struct Dims {
@@ -27,6 +28,7 @@ inline int check_shape(const moe_shape* s, Dims* out) {
   if (s->T < 0 || s->E < 1 || s->k < 1 || s->k > s->E || s->E_shared < 0) return MOE_ERR_SHAPE;
   if (s->E > kMaxExperts || (long long)s->E + s->E_shared > kMaxExperts) return MOE_ERR_SHAPE;
   if (s->d_model <= 0 || s->d_ffn <= 0 || (s->d_model % 64) || (s->d_ffn % 64)) return MOE_ERR_SHAPE;
+  if (s->d_model > kMaxWidth || s->d_ffn > kMaxWidth) return MOE_ERR_SHAPE;  // 32-bit per-lane byte offsets in the GEMM loads
   long long Kp = (long long)s->k + s->E_shared;
   long long N = (long long)s->T * Kp;
   if (N >= (1ll << 31)) return MOE_ERR_SHAPE;

@@ -1,6 +1,6 @@
 // Grouped bf16 MFMA GEMMs of the SwiGLU expert FFNs over ragged per-expert row segments, forward and backward
-// (Section III-A: W_up, W_gate in R^{d x f}, W_down in R^{f x d}, per-expert token counts s_e; the "imbalanced
-// tall-and-skinny GEMMs" of the abstract and Section II-A).
+// (Section III-A: W_up, W_gate in R^{d x f}, W_down in R^{f x d}, per-expert token counts s_e; these are the
+// per-expert GEMMs of uneven, often small row counts that the abstract and Section II-A single out).
 //
 // One kernel template serves all seven contractions.  Every output tile is
 //     C[p, q] = sum_k  P[p, k] * Q[q, k]          (p: 256 values, q: 256 values, k in steps of 64)

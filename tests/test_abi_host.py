@@ -44,6 +44,9 @@ def test_workspace_bytes_follows_the_shape(lib):
     assert moe.workspace_bytes(moe.Shape(256, 512, 1024, 8, 9)) == 0       # k > E
     assert moe.workspace_bytes(moe.Shape(256, 512, 1024, 2000, 2)) == 0    # E over the limit
     assert moe.workspace_bytes(moe.Shape(2 ** 30, 512, 1024, 8, 2)) == 0   # T*K' >= 2^31
+    assert moe.workspace_bytes(moe.Shape(1, 2 ** 22, 64, 8, 2)) > 0        # the widest rows the GEMM loads can address
+    assert moe.workspace_bytes(moe.Shape(1, 2 ** 22 + 64, 64, 8, 2)) == 0  # beyond: the 32-bit row offsets would wrap
+    assert moe.workspace_bytes(moe.Shape(1, 64, 2 ** 22 + 64, 8, 2)) == 0
 
 
 def _shape(**kw):
@@ -75,6 +78,8 @@ def test_argument_checks_run_before_any_launch(lib):
     assert lib.moe_grouped_ffn_fwd(sp, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 16, None) == -4
     assert lib.moe_grouped_ffn_fwd(sp, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == -1
     assert lib.moe_grouped_ffn_fwd(bad, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == -2
+    wide = ctypes.byref(_shape(d_model=2 ** 22 + 64)._c)
+    assert lib.moe_grouped_ffn_fwd(wide, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == -2
     assert lib.moe_grouped_ffn_bwd(sp, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0,
                                    FAKE, 1 << 40, None) == -1
     assert lib.moe_grouped_ffn_bwd(sp, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0,

@@ -524,6 +524,92 @@ def test_error_measures_and_scales():
         assert np.all(sc[key] * math.sqrt(n_terms) >= np.abs(g[key]) - 1e-12)     # Cauchy-Schwarz
 
 
+@pytest.mark.parametrize("renorm", [True, False])
+def test_gate_of_a_given_selection_matches_loops(renorm):
+    """gate_of_selection on a choice that is NOT the top-k (any distinct experts, any order): the weights are the
+    softmax probabilities of the chosen experts (over their sum when renormalised), by pure-Python loops."""
+    rng = np.random.default_rng(8)
+    T, E, k, Es = 9, 6, 3, 2
+    logits = rng.standard_normal((T, E)) * 2
+    sel = np.stack([rng.permutation(E)[:k] for _ in range(T)])
+    idx, w, probs = O.gate_of_selection(logits, sel, Es, renorm)
+    for t in range(T):
+        p = py_softmax(list(logits[t]))
+        ws = [p[e] for e in sel[t]]
+        if renorm:
+            tot = sum(ws)
+            ws = [v / tot for v in ws]
+        assert list(idx[t]) == list(sel[t]) + [E, E + 1]
+        assert all(abs(w[t, j] - ws[j]) < 1e-15 for j in range(k)) and list(w[t, k:]) == [1.0, 1.0]
+        assert all(abs(probs[t, e] - p[e]) < 1e-15 for e in range(E))
+
+
+def test_scales_are_the_size_of_the_error_of_perturbed_operands():
+    """Pins every *_scales function from BOTH sides.  Each float operand of a stage is multiplied by (1 + s*n) with
+    n ~ N(0,1) and s = 2^-9 (half a bf16 ulp, the rounding a reduced-precision evaluation applies), the stage is
+    re-evaluated in float64, and over many draws the rms error of every single output element must lie within
+    [0.3, 3] x s x (its scale).  A scale that is several times too large (which would loosen every element-wise
+    parity bound) or too small fails; so does one whose propagation through the SwiGLU chain drops a term."""
+    sig, draws = 2.0 ** -9, 200
+    rng = np.random.default_rng(5)
+
+    def noisy(a):
+        return a * (1.0 + sig * rng.standard_normal(a.shape))
+
+    def check(name, ref, scale, samples):
+        err = np.sqrt(np.mean([(s - ref) ** 2 for s in samples], axis=0))
+        m = scale > 0
+        assert np.all(err[~m] == 0.0), name                      # scale 0 only where nothing can move
+        ratio = err[m] / (sig * scale[m])
+        assert 0.3 <= ratio.min() and ratio.max() <= 3.0, (name, ratio.min(), ratio.max())
+
+    x, Wg, Wu, Wd, logits, dout = small_case(T=24, d=12, f=10, E=4, k=2, E_shared=1, seed=11)
+    logits[:, 3] = -1e30                                          # one empty expert
+    Et, Kp = 5, 3
+    idx, w, _ = O.route_topk(logits, 2, 1, True)
+    counts, offsets, ros, sor = O.permute_maps(idx, Et)
+    assert counts[3] == 0
+    xp = O.permute_rows(x, sor, Kp)
+    dyp = rng.standard_normal(xp.shape) * rng.random((xp.shape[0], 1))
+
+    ref = O.grouped_ffn_fwd(xp, offsets, Wg, Wu, Wd)
+    sc = O.grouped_ffn_fwd_scales(xp, offsets, Wg, Wu, Wd)
+    smp = [O.grouped_ffn_fwd(noisy(xp), offsets, noisy(Wg), noisy(Wu), noisy(Wd)) for _ in range(draws)]
+    for i, name in enumerate(("Y", "G", "U")):
+        check("fwd " + name, ref[i], sc[i], [s[i] for s in smp])
+
+    ref = O.grouped_ffn_bwd(dyp, xp, offsets, Wg, Wu, Wd)
+    sc = O.grouped_ffn_bwd_scales(dyp, xp, offsets, Wg, Wu, Wd)
+    smp = [O.grouped_ffn_bwd(noisy(dyp), noisy(xp), offsets, noisy(Wg), noisy(Wu), noisy(Wd)) for _ in range(draws)]
+    for i, name in enumerate(("dX", "dWg", "dWu", "dWd")):
+        check("bwd " + name, ref[i], sc[i], [s[i] for s in smp])
+
+    out, _ = O.layer_forward(x, idx, w, Wg, Wu, Wd)
+    g = O.layer_backward(x, idx, w, Wg, Wu, Wd, dout)
+    outs, gs = [], []
+    for _ in range(draws):
+        a = (noisy(x), idx, noisy(w), noisy(Wg), noisy(Wu), noisy(Wd))
+        outs.append(O.layer_forward(*a)[0])
+        gs.append(O.layer_backward(*a, noisy(dout)))
+    for fn in (O.layer_scales, O.layer_scales_staged):
+        sc = fn(x, idx, w, Wg, Wu, Wd, dout, Et)
+        check(fn.__name__ + " out", out, sc["out"], outs)
+        for key in ("dx", "dtopk_w", "dw_gate", "dw_up", "dw_down"):
+            check(fn.__name__ + " " + key, g[key], sc[key], [s[key] for s in gs])
+
+    ym, wt = rng.standard_normal((ros.size, 7)), rng.random(w.shape)
+    check("combine", O.unpermute_combine(ym, ros, wt), O.unpermute_combine_scale(np.abs(ym), ros, wt),
+          [O.unpermute_combine(noisy(ym), ros, noisy(wt)) for _ in range(draws)])
+
+    wr, dl = rng.standard_normal((4, 12)) * 0.3, rng.standard_normal((24, 4))
+    ql, qx, qw = O.router_scales(x, wr, dl)
+    check("logits", O.router_logits(x, wr), ql, [O.router_logits(noisy(x), noisy(wr)) for _ in range(draws)])
+    ref = O.router_logits_bwd(x, wr, dl)
+    smp = [O.router_logits_bwd(noisy(x), noisy(wr), noisy(dl)) for _ in range(draws)]
+    check("dx_router", ref[0], qx, [s[0] for s in smp])
+    check("dw_router", ref[1], qw, [s[1] for s in smp])
+
+
 # ---------------------------------------------------------------------------------------------------------
 # workloads (input recipes) -- structure checks that use the oracle's routing
 # ---------------------------------------------------------------------------------------------------------
