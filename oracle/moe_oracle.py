@@ -674,35 +674,38 @@ def load_imbalance(load, groups):
 
 
 def rebalance_hill_climbing(load, groups, max_iters=100):
-    """The swap rebalancer of Section VI, Algorithm 2.
+    """The swap rebalancer of Section VI, Algorithm 2, by brute force from what a step means.
 
-    Each iteration takes the group with the largest sum (k+) and the one with the smallest (k-); among all swaps of
-    one expert of k+ with one of k- it takes the one that shrinks |s_{k+} - s_{k-}| the most (it must shrink it), and
-    stops when no swap does.  Readings where the listing is silent: arg max / arg min and the best swap keep the
-    first candidate on ties (groups and their members are scanned in stored order), and a swap exchanges the two
-    experts in place (each takes the other's position).  Returns (groups, swaps) with swaps = [(expert from k+,
-    expert from k-), ...] in the order performed; the input is not modified."""
-    G = [list(g) for g in groups]
+    A step looks at the group with the largest summed load and the one with the smallest.  Every exchange of one
+    expert of the former with one of the latter is actually carried out on a copy of the placement, the two sums are
+    recomputed from scratch, and the exchange that leaves the smallest difference between them wins, provided that
+    difference is smaller than before; if none is, the search ends.  Readings where the paper is silent: the largest /
+    smallest group and the winning exchange are the first ones in stored order among equals (groups, then members of
+    the heavy group, then members of the light group), and an exchange puts each expert in the other's position.
+    Returns (groups, swaps) with swaps = [(expert that left the heavy group, expert that left the light group), ...]
+    in the order performed; the input is not modified."""
+    placement = [list(g) for g in groups]
     swaps = []
     for _ in range(max_iters):
-        s = group_loads(load, G)
-        k_plus = max(range(len(G)), key=lambda k: (s[k], -k))
-        k_minus = min(range(len(G)), key=lambda k: (s[k], k))
-        delta = s[k_plus] - s[k_minus]
-        best, best_gain = None, 0
-        for i, e1 in enumerate(G[k_plus]):
-            n1 = int(load[e1])
-            for j, e2 in enumerate(G[k_minus]):
-                n2 = int(load[e2])
-                d2 = abs((s[k_plus] - n1 + n2) - (s[k_minus] - n2 + n1))
-                if d2 < delta and (delta - d2) > best_gain:
-                    best_gain, best = delta - d2, (i, j)
-        if best is None:
+        sums = group_loads(load, placement)
+        heavy = sums.index(max(sums))
+        light = sums.index(min(sums))
+        before = sums[heavy] - sums[light]
+        candidates = []
+        for i in range(len(placement[heavy])):
+            for j in range(len(placement[light])):
+                trial = [list(g) for g in placement]
+                trial[heavy][i], trial[light][j] = trial[light][j], trial[heavy][i]
+                after = group_loads(load, trial)
+                candidates.append((abs(after[heavy] - after[light]), i, j))
+        if not candidates:
             break
-        i, j = best
-        swaps.append((G[k_plus][i], G[k_minus][j]))
-        G[k_plus][i], G[k_minus][j] = G[k_minus][j], G[k_plus][i]
-    return G, swaps
+        after, i, j = min(candidates)          # smallest remaining difference; first (i, j) among equals
+        if after >= before:
+            break
+        swaps.append((placement[heavy][i], placement[light][j]))
+        placement[heavy][i], placement[light][j] = placement[light][j], placement[heavy][i]
+    return placement, swaps
 
 
 # --------------------------------------------------------------------------------------------------------------
@@ -710,7 +713,7 @@ def rebalance_hill_climbing(load, groups, max_iters=100):
 #
 # One rank holds a send buffer S [N, D] with N = num_nodes * R rows (R = ranks per node): row n*R + l goes to local
 # rank l of node n.  The algorithm's own steps that touch only this rank's memory are written out below in its
-# notation; the exchanges between ranks are not part of this library (halo_all_to_all_reference simulates them
+# notation as the row maps they define; the exchanges between ranks are not part of this library (halo_all_to_all_reference simulates them
 # on the host only to pin the local steps against the definition of an all-to-all).
 # --------------------------------------------------------------------------------------------------------------
 def halo_remote_nodes(num_nodes, node_id):
@@ -719,33 +722,42 @@ def halo_remote_nodes(num_nodes, node_id):
 
 
 def halo_pack_remote(S, num_nodes, R, node_id):
-    """Phase 2 pack: F2s = IndexSelect(S, idx) with idx = [n R, ..., n R + R - 1 | n in N_-]; shape [M R, D]."""
+    """Phase 2 pack, as the row map it defines: row i R + r of the packed buffer is the row of S addressed to local
+    rank r of the i-th remote node.  Shape [M R, D]."""
     S = np.asarray(S)
-    idx = [n * R + r for n in halo_remote_nodes(num_nodes, node_id) for r in range(R)]
-    return S[idx]
+    rem = halo_remote_nodes(num_nodes, node_id)
+    out = np.empty((len(rem) * R,) + S.shape[1:], dtype=S.dtype)
+    for i, n in enumerate(rem):
+        for r in range(R):
+            out[i * R + r] = S[n * R + r]
+    return out
 
 
 def halo_repack_phase3(F2r, M, R):
-    """Phase 3 repack: view F2r as (M, R, D), permute to (R, M, D), flatten to [R, M D]: row l = everything the
-    remote nodes sent for local rank l."""
+    """Phase 3 repack, as the map it defines: the received buffer holds, for the i-th remote node, one row per local
+    rank r (row i R + r); output row r is the concatenation over i of those rows, i.e. everything the remote nodes
+    sent for local rank r.  Shape [R, M D]."""
     F2r = np.asarray(F2r)
     D = F2r.shape[1]
-    return np.ascontiguousarray(F2r.reshape(M, R, D).transpose(1, 0, 2)).reshape(R, M * D)
+    out = np.empty((R, M * D), dtype=F2r.dtype)
+    for r in range(R):
+        for i in range(M):
+            out[r, i * D:(i + 1) * D] = F2r[i * R + r]
+    return out
 
 
 def halo_unpack_output(P1, F3r, num_nodes, R, node_id):
-    """Final placement: O[local_start : local_start + R] = P1; T = permute(view(F3r, R, M, D), [1,0,2]);
-    O[n R : (n+1) R] = T[i] for the i-th remote node n."""
+    """Final placement, as the map it defines: output row n R + p is what rank p of node n sent to this rank.  The own
+    node's R rows are the phase-1 result; the i-th remote node's row p is the i-th D-wide piece of row p of the
+    phase-3 result."""
     P1, F3r = np.asarray(P1), np.asarray(F3r)
     D = P1.shape[1]
-    rem = halo_remote_nodes(num_nodes, node_id)
-    M = len(rem)
-    O = np.empty((num_nodes * R, D), dtype=P1.dtype)
-    O[node_id * R:(node_id + 1) * R] = P1
-    Tm = F3r.reshape(R, M, D).transpose(1, 0, 2)
-    for i, n in enumerate(rem):
-        O[n * R:(n + 1) * R] = Tm[i]
-    return O
+    out = np.empty((num_nodes * R, D), dtype=P1.dtype)
+    for p in range(R):
+        out[node_id * R + p] = P1[p]
+        for i, n in enumerate(halo_remote_nodes(num_nodes, node_id)):
+            out[n * R + p] = F3r[p, i * D:(i + 1) * D]
+    return out
 
 
 def halo_all_to_all_reference(send, num_nodes, R):

@@ -1,5 +1,5 @@
-"""Load statistics and the hill-climbing swap rebalancer (Section VI, Algorithm 2): pins of the oracle, then the
-library's host implementation against the oracle, bit for bit (integers; no GPU involved)."""
+"""Load statistics and the swap rebalancer (Section VI, Algorithm 2): pins of the oracle (a brute force over all
+exchanges), then the library's host implementation (a sorted search) against it, bit for bit (integers; no GPU)."""
 import itertools
 import os
 
@@ -112,6 +112,22 @@ def test_library_matches_oracle(seed):
     assert got_groups.tolist() == ref_groups
     assert got_swaps.tolist() == [list(s) for s in ref_swaps]
     assert abs(moe.load_imbalance(load, got_groups) - O.load_imbalance(load, ref_groups)) < 1e-12
+
+
+def test_library_matches_oracle_on_tie_heavy_loads():
+    """Loads from a handful of values, so that many exchanges are equally good: the first in stored order must win."""
+    moe.load_library()
+    rng = np.random.default_rng(7)
+    n_swaps = 0
+    for _ in range(150):
+        K, m = int(rng.integers(1, 7)), int(rng.integers(1, 12))
+        load = rng.integers(0, int(rng.choice([3, 10, 100])), size=K * m).astype(np.int64)
+        groups = rng.permutation(K * m).astype(np.int32).reshape(K, m)
+        ref_groups, ref_swaps = O.rebalance_hill_climbing(load, groups.tolist(), max_iters=50)
+        got_groups, got_swaps = moe.rebalance_experts(load, groups, max_iters=50)
+        assert got_groups.tolist() == ref_groups and got_swaps.tolist() == [list(s) for s in ref_swaps]
+        n_swaps += len(ref_swaps)
+    assert n_swaps > 100
 
 
 def test_library_golden_and_statistics():
