@@ -123,6 +123,16 @@ int moe_permute(const moe_shape* shape, const uint16_t* x, const int32_t* topk_i
                 int32_t* counts, int32_t* offsets, int32_t* row_of_slot, int32_t* slot_of_row,
                 void* ws, size_t ws_bytes, void* stream);
 
+/* moe_permute for callers that cannot allocate device memory or bring a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments without `ws`, same results bit for bit.  The
+ * scratch (per-slot ranks, per-block histograms) is an 8 MiB array that lives in the library's device image on every
+ * GPU for the life of the process, so the call allocates nothing.  Limits: T*K' <= 2^20 and
+ * ceil(T*K'/1024) * E' <= 2^20, else MOE_ERR_WORKSPACE (nothing enqueued).  Every call on a GPU shares that GPU's
+ * array: calls that may overlap on one GPU (different streams, different host threads) race and must be ordered
+ * by the caller.  Nothing in the array has to survive between calls or start at zero. */
+int moe_permute_noalloc(const moe_shape* shape, const uint16_t* x, const int32_t* topk_idx, uint16_t* x_perm,
+                        int32_t* counts, int32_t* offsets, int32_t* row_of_slot, int32_t* slot_of_row, void* stream);
+
 /* Derivative of the row copy: dx[t] = sum_j dx_perm[row_of_slot[t*K'+j]] (fp32 sum in slot order, one bf16
  * rounding).   dx_perm [N,d] bf16 in;  dx [T,d] bf16 out. */
 int moe_permute_bwd(const moe_shape* shape, const uint16_t* dx_perm, const int32_t* row_of_slot,

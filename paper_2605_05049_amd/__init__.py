@@ -6,7 +6,7 @@ library is missing, calls raise.
 """
 from .binding import (  # noqa: F401
     MoeError, Shape, abi_version, load_library, library_path, status_str, workspace_bytes,
-    moe_route_topk, moe_route_topk_bwd, moe_permute, moe_permute_bwd, moe_permute_bwd_add, moe_router_fwd,
+    moe_route_topk, moe_route_topk_bwd, moe_permute, moe_permute_noalloc, moe_permute_bwd, moe_permute_bwd_add, moe_router_fwd,
     moe_router_bwd, moe_grouped_ffn_bwd_recompute, moe_grouped_ffn_fwd,
     moe_grouped_ffn_bwd, moe_unpermute_combine, moe_unpermute_combine_bwd, EXPORTED_SYMBOLS,
     profile_enable, profile_reset, profile_records, load_accumulate, load_imbalance, rebalance_experts,

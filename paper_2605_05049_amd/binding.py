@@ -13,7 +13,7 @@ _lib = None
 EXPORTED_SYMBOLS = (
     "moe_status_str", "moe_workspace_bytes", "moe_abi_version",
     "moe_profile_enable", "moe_profile_count", "moe_profile_get", "moe_profile_reset",
-    "moe_route_topk", "moe_route_topk_bwd", "moe_permute", "moe_permute_bwd", "moe_permute_bwd_add",
+    "moe_route_topk", "moe_route_topk_bwd", "moe_permute", "moe_permute_noalloc", "moe_permute_bwd", "moe_permute_bwd_add",
     "moe_router_fwd", "moe_router_bwd", "moe_grouped_ffn_fwd", "moe_grouped_ffn_bwd", "moe_grouped_ffn_bwd_recompute",
     "moe_unpermute_combine", "moe_unpermute_combine_bwd",
     "moe_load_accumulate", "moe_load_imbalance", "moe_rebalance_experts",
@@ -85,6 +85,7 @@ def load_library():
         "moe_route_topk": [sp, V, V, V, V, V],
         "moe_route_topk_bwd": [sp, V, V, V, V, V, V],
         "moe_permute": [sp, V, V, V, V, V, V, V, V, c_size_t, V],
+        "moe_permute_noalloc": [sp, V, V, V, V, V, V, V, V],
         "moe_permute_bwd": [sp, V, V, V, V],
         "moe_permute_bwd_add": [sp, V, V, V, V, V],
         "moe_router_fwd": [sp, V, V, V, V, c_size_t, V],
@@ -214,6 +215,18 @@ def moe_permute(shape, x, topk_idx, x_perm, counts, offsets, row_of_slot, slot_o
         _ptr(slot_of_row, torch.int32, s.N, "slot_of_row"), _ptr(ws, None, None, "ws"),
         ws.numel() * ws.element_size(), _stream(stream))
     _check("moe_permute", rc)
+
+
+def moe_permute_noalloc(shape, x, topk_idx, x_perm, counts, offsets, row_of_slot, slot_of_row, stream=None):
+    import torch
+    s = Shape.of(shape)
+    bf = _bf16_types()
+    rc = load_library().moe_permute_noalloc(
+        ctypes.byref(s._c), _ptr(x, bf, s.T * s.d_model, "x"), _ptr(topk_idx, torch.int32, s.N, "topk_idx"),
+        _ptr(x_perm, bf, s.N * s.d_model, "x_perm"), _ptr(counts, torch.int32, s.E_total, "counts"),
+        _ptr(offsets, torch.int32, s.E_total + 1, "offsets"), _ptr(row_of_slot, torch.int32, s.N, "row_of_slot"),
+        _ptr(slot_of_row, torch.int32, s.N, "slot_of_row"), _stream(stream))
+    _check("moe_permute_noalloc", rc)
 
 
 def moe_permute_bwd(shape, dx_perm, row_of_slot, dx, stream=None):

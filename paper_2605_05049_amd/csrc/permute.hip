@@ -12,6 +12,8 @@
 // The copy kernels are pure HBM streaming with 16-byte accesses per lane.
 #include "common.h"
 
+#include <mutex>
+
 namespace moe {
 
 constexpr int kSub = kPermSlotsPerBlock / kWave;  // 16 sub-groups of 64 slots per block
@@ -355,24 +357,26 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restric
 
 }  // namespace moe
 
-extern "C" int moe_permute(const moe_shape* shape, const uint16_t* x, const int32_t* topk_idx, uint16_t* x_perm,
-                           int32_t* counts, int32_t* offsets, int32_t* row_of_slot, int32_t* slot_of_row,
-                           void* ws, size_t ws_bytes, void* stream) {
-  using namespace moe;
-  Dims D;
-  int rc = check_shape(shape, &D);
+namespace moe {
+
+// Host-side argument checks shared by the two entry points of the permutation.
+static int permute_checks(const moe_shape* shape, Dims* D, const uint16_t* x, const int32_t* topk_idx, uint16_t* x_perm,
+                          int32_t* counts, int32_t* offsets, int32_t* row_of_slot, int32_t* slot_of_row) {
+  int rc = check_shape(shape, D);
   if (rc != MOE_OK) return rc;
   MOE_REQUIRE_PTR(topk_idx); MOE_REQUIRE_PTR(counts); MOE_REQUIRE_PTR(offsets); MOE_REQUIRE_PTR(row_of_slot);
-  MOE_REQUIRE_PTR(slot_of_row); MOE_REQUIRE_PTR(ws);
+  MOE_REQUIRE_PTR(slot_of_row);
   if ((x == nullptr) != (x_perm == nullptr)) return MOE_ERR_NULL;
   MOE_REQUIRE_ALIGNED(x); MOE_REQUIRE_ALIGNED(topk_idx); MOE_REQUIRE_ALIGNED(x_perm); MOE_REQUIRE_ALIGNED(counts);
   MOE_REQUIRE_ALIGNED(offsets); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(slot_of_row);
-  if (!aligned(ws, 256)) return MOE_ERR_ALIGN;
-  const WsLayout L = ws_layout(D);
-  if (ws_bytes < L.total) return MOE_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
-  int32_t* block_hist = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.perm_hist);
-  int32_t* lrank = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.perm_rank);
+  return MOE_OK;
+}
+
+// The three launches of the counting sort.  block_hist: perm_num_blocks(N) * E' int32; lrank: N int32.  Every entry of
+// both that a later kernel reads is written by an earlier one of the same call, so neither has to start at zero.
+static int permute_launch(const Dims& D, const uint16_t* x, const int32_t* topk_idx, uint16_t* x_perm, int32_t* counts,
+                          int32_t* offsets, int32_t* row_of_slot, int32_t* slot_of_row, int32_t* block_hist, int32_t* lrank,
+                          hipStream_t st) {
   const int nblk = perm_num_blocks(D.N);
   int nbits = 0;
   while ((1 << nbits) < D.Et) nbits++;
@@ -388,6 +392,63 @@ extern "C" int moe_permute(const moe_shape* shape, const uint16_t* x, const int3
                                      row_of_slot, slot_of_row, D.T, D.Kp, D.Et, D.d / 8));
   }
   return launch_status();
+}
+
+// Scratch of moe_permute_noalloc: the per-slot ranks (kNoAllocMaxSlots int32) followed by the per-block histograms
+// (kNoAllocMaxHist int32), 8 MiB in all, resident on every GPU the library runs on until the process ends.
+constexpr long long kNoAllocMaxSlots = 1ll << 20;   // T*K' limit
+constexpr long long kNoAllocMaxHist = 1ll << 20;    // ceil(T*K'/1024) * E' limit
+static __device__ __align__(256) int32_t scratch[kNoAllocMaxSlots + kNoAllocMaxHist];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static int32_t* scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, looked up on first use
+
+// The array's name is only a host-side handle: its device address (one per GPU) comes from the runtime.
+static int scratch_on_current_device(int32_t** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_RUNTIME;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return MOE_ERR_RUNTIME;
+    scratch_ptr[dev] = static_cast<int32_t*>(p);
+  }
+  *out = scratch_ptr[dev];
+  return MOE_OK;
+}
+
+}  // namespace moe
+
+extern "C" int moe_permute(const moe_shape* shape, const uint16_t* x, const int32_t* topk_idx, uint16_t* x_perm,
+                           int32_t* counts, int32_t* offsets, int32_t* row_of_slot, int32_t* slot_of_row,
+                           void* ws, size_t ws_bytes, void* stream) {
+  using namespace moe;
+  Dims D;
+  int rc = permute_checks(shape, &D, x, topk_idx, x_perm, counts, offsets, row_of_slot, slot_of_row);
+  if (rc != MOE_OK) return rc;
+  MOE_REQUIRE_PTR(ws);
+  if (!aligned(ws, 256)) return MOE_ERR_ALIGN;
+  const WsLayout L = ws_layout(D);
+  if (ws_bytes < L.total) return MOE_ERR_WORKSPACE;
+  return permute_launch(D, x, topk_idx, x_perm, counts, offsets, row_of_slot, slot_of_row,
+                        reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.perm_hist),
+                        reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.perm_rank), (hipStream_t)stream);
+}
+
+extern "C" int moe_permute_noalloc(const moe_shape* shape, const uint16_t* x, const int32_t* topk_idx, uint16_t* x_perm,
+                                   int32_t* counts, int32_t* offsets, int32_t* row_of_slot, int32_t* slot_of_row,
+                                   void* stream) {
+  using namespace moe;
+  Dims D;
+  int rc = permute_checks(shape, &D, x, topk_idx, x_perm, counts, offsets, row_of_slot, slot_of_row);
+  if (rc != MOE_OK) return rc;
+  if (D.N > kNoAllocMaxSlots || (long long)perm_num_blocks(D.N) * D.Et > kNoAllocMaxHist) return MOE_ERR_WORKSPACE;
+  int32_t* base = nullptr;
+  rc = scratch_on_current_device(&base);
+  if (rc != MOE_OK) return rc;
+  return permute_launch(D, x, topk_idx, x_perm, counts, offsets, row_of_slot, slot_of_row, base + kNoAllocMaxSlots, base,
+                        (hipStream_t)stream);
 }
 
 extern "C" int moe_permute_bwd(const moe_shape* shape, const uint16_t* dx_perm, const int32_t* row_of_slot,
