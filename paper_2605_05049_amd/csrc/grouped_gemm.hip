@@ -33,11 +33,14 @@
 // tiles so that tiles sharing a weight panel meet in one L2.
 #include "common.h"
 
+#include <type_traits>
+
 namespace moe {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;                          // k step
 constexpr int TILE = 256;                       // p extent, and (virtual) q extent, of a block tile
@@ -120,8 +123,10 @@ __device__ __forceinline__ unsigned load_offset(const TileOperand& op, int n, in
 // Written as inline assembly on purpose: the compiler does not track it, so it never makes the (transposing)
 // fragment reads of the OTHER stage wait for loads still in flight.  The kernel orders these loads itself: an
 // explicit s_waitcnt vmcnt(0) precedes the barrier that publishes a stage, and no compiler-tracked vector-memory
-// load is in flight while these are (the epilogue starts after the last such wait).  Two address forms: a 64-bit
-// address per lane, or a scalar base plus a 32-bit byte offset per lane.
+// load is in flight while these are (the epilogue starts after the last such wait).  m0 receives the LDS base: the
+// backend reserves m0 (it is never allocated, and the compiler writes it only directly before an instruction of its
+// own that reads it; this kernel has none: no LDS-direct or GDS access, no register-indexed moves, no messages).  Two
+// address forms: a 64-bit address per lane, or a scalar base plus a 32-bit byte offset per lane.
 __device__ __forceinline__ void direct_load16(const void* g, const char* lds_dst) {
   const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)lds_dst);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(g) : "memory");
@@ -142,9 +147,10 @@ __device__ __forceinline__ void issue_tile(const unsigned (&voff)[4], const Tile
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const int n = wave * 4 + i;
-    // NARROW (the router's skinny problems): instructions that would only fetch rows or columns past the operand's
-    // valid extent are left out; those LDS rows then hold stale data, which only ever reaches accumulators that are
-    // never stored (an accumulator row or column depends on its own operand row alone)
+    // Instructions that would only fetch rows or columns past the operand's valid extent are left out (short row
+    // tiles, the last column tile of a width that is not a multiple of 256, the router's skinny problems); those LDS
+    // rows then hold stale data, which only ever reaches accumulators that are never stored (an accumulator row or
+    // column depends on its own operand row alone)
     if (NARROW && (RC ? (!SPLIT && (n & 1) && op.r_valid <= 128) : n * 8 >= op.r_valid)) continue;
     const uint16_t* sb = ((RC && SPLIT && (n & 1)) ? op.base1 : op.base0) + delta + (RC ? (size_t)k0 * op.ld : (size_t)k0);
     if (RC && k0 + BK > k_end) {  // the ragged end of K: k-rows past it come from the zeroed page
@@ -155,6 +161,14 @@ __device__ __forceinline__ void issue_tile(const unsigned (&voff)[4], const Tile
       direct_load16(sb, voff[i], lds_tile + n * 1024);
     }
   }
+}
+
+// 16 bytes that another CU has written during this launch: read at agent scope, so that this CU's vector L1 is
+// bypassed whatever it holds (the partial tiles of a split K range).
+__device__ __forceinline__ f32x4 load_agent_f4(const float* p) {
+  f32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+  return v;
 }
 
 // MFMA operand fragment: 32 r-values x 16 k-values; lane l gets r = r0 + l%32, k = kk + 8*(l/32) .. +7.
@@ -196,7 +210,6 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wp = (wave & 1) * 128;  // p origin of this wavefront
   const int wq = wave >> 1;         // 0..3 along q
   const int late = wave >> 2;       // wavefronts 4..7 share their SIMDs with 0..3 and load at another time of the step
 
@@ -280,14 +293,6 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   }
   const int q_valid = min(TQ, A.q_dim - q0_col);
 
-  f32x16 acc[2][4];  // [q sub-tile a][p sub-tile b]
-#pragma unroll
-  for (int a = 0; a < 2; a++)
-#pragma unroll
-    for (int b = 0; b < 4; b++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) acc[a][b][v] = 0.f;
-
   // LDS row origin of this wavefront's two q fragments
   const int qr0 = (NQ == 2) ? wq * 32 : wq * 64;
   const int qr1 = (NQ == 2) ? 128 + wq * 32 : wq * 64 + 32;
@@ -322,7 +327,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   // Each half of the shared panel is then requested right after the barrier by half of its users, and the requests
   // the other half makes half a step later find it in, or on its way to, the L2.  (Left out where it measured
   // slower or was not measured: the forward down projection and the router's skinny problems.)
-  constexpr bool ALTERNATE_Q = !NARROW && !(KIND == 0 && Q_RC && NQ == 1 && EPI == EPI_BF16);
+  constexpr bool ALTERNATE_Q = !(KIND == 0 && EPI == EPI_F32) && !(KIND == 0 && Q_RC && NQ == 1 && EPI == EPI_BF16);
   const int iwq = ALTERNATE_Q ? (wave ^ ((p_tile_idx & 1) << 2)) : wave;
   unsigned pvo[4], qvo[4];
 #pragma unroll
@@ -333,16 +338,32 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   const int nk_pass = (k_len + BK - 1) / BK;  // k-steps per K pass
   const int nk = nk_pass * NPASS;             // k-steps of the whole contraction
   // this wavefront's 8 direct loads of step j of the contraction
-  auto issue = [&](int j, char* stage) {
+  auto issue_as = [&](auto narrow_p, int j, char* stage) __attribute__((always_inline)) {
     const bool second = (NPASS == 2) && j >= nk_pass;
     const int k0 = (second ? j - nk_pass : j) * BK;
-    issue_tile<P_RC, false, NARROW>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage, wave, lane);
+    issue_tile<P_RC, false, decltype(narrow_p)::value>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage, wave, lane);
     issue_tile<Q_RC, NQ == 2, NARROW>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + OPERAND_BYTES, iwq, lane);
   };
   // the k-steps this block multiplies: all of them, or its part of a split tile
   const int kt_per = (nk + split - 1) / split;
   const int kt_begin = part * kt_per, kt_end = min(nk, kt_begin + kt_per);
-  if (kt_begin < kt_end) issue(kt_begin, stage0);
+  // (the first stage is requested before anything else is set up; rows a short tile does not have are clamped here)
+  if (kt_begin < kt_end) issue_as(std::integral_constant<bool, NARROW>{}, kt_begin, stage0);
+  // Height class of the tile: each of the two wavefronts along p multiplies PB blocks of 32 rows (4, 2 or 1), so a
+  // ragged last row tile of an expert issues MFMAs and row loads for its class (256, 128 or 64 rows) only.
+  auto run = [&](auto pb_c) __attribute__((always_inline)) {
+  constexpr int PB = decltype(pb_c)::value;
+  // (a short tile leaves out the loads of the rows it does not have)
+  auto issue = [&](int j, char* stage) __attribute__((always_inline)) { issue_as(std::integral_constant<bool, NARROW || PB < 4>{}, j, stage); };
+  const int wp = (wave & 1) * (PB * 32);  // p origin of this wavefront
+  f32x16 acc[2][PB];  // [q sub-tile a][p sub-tile b]
+#pragma unroll
+  for (int a = 0; a < 2; a++)
+#pragma unroll
+    for (int b = 0; b < PB; b++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[a][b][v] = 0.f;
+
   // One k-step: wait for stage `cur`, multiply it, and meanwhile fill `nxt` with step kt+1.  The two wavefronts of a
   // SIMD request their share of the next stage at different times of the step (one before its MFMAs, the other
   // between its two halves of them), so that while one is held up issuing loads the other keeps the matrix pipe busy.
@@ -359,13 +380,13 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
         if (!late && kt + 1 < kt_end) issue(kt + 1, nxt);
         __builtin_amdgcn_sched_barrier(0);
       }
-      bf16x8 pf[4], qf[2];
+      bf16x8 pf[PB], qf[2];
       qf[0] = read_frag<Q_RC>(q_lds, qr0, kk, lane);
       qf[1] = read_frag<Q_RC>(q_lds, qr1, kk, lane);
 #pragma unroll
-      for (int b = 0; b < 4; b++) pf[b] = read_frag<P_RC>(p_lds, wp + 32 * b, kk, lane);
+      for (int b = 0; b < PB; b++) pf[b] = read_frag<P_RC>(p_lds, wp + 32 * b, kk, lane);
 #pragma unroll
-      for (int b = 0; b < 4; b++)
+      for (int b = 0; b < PB; b++)
 #pragma unroll
         for (int a = 0; a < 2; a++)
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[a], pf[b], acc[a][b], 0, 0, 0);
@@ -392,7 +413,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     // ---- a part of a split tile: fp32 partial tile -> workspace, then whoever arrives last reduces
     float* mine = A.partial + (size_t)part_slot * (TILE * TILE);
 #pragma unroll
-    for (int b = 0; b < 4; b++) {
+    for (int b = 0; b < PB; b++) {
 #pragma unroll
       for (int a = 0; a < 2; a++)
 #pragma unroll
@@ -415,8 +436,8 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
       __builtin_amdgcn_wave_barrier();
     }
     // All parts of a tile carry the same blockIdx.x % 8 and so run on one XCD, whose L2 they share: a store that has
-    // been acknowledged (vmcnt) is then visible to the other parts, and no cache has to be written back or
-    // invalidated.  That placement is checked, not assumed: a part that finds itself on another XCD falls back to
+    // been acknowledged (vmcnt) is then visible to the other parts at the L2, and no cache has to be written back or
+    // invalidated; the reducing part reads the partial tiles at agent scope, i.e. past its own vector L1.  That placement is checked, not assumed: a part that finds itself on another XCD falls back to
     // device-wide fences and says so in the upper half of the counter, which makes the reducing part fence as well.
     __shared__ int arrived_before;
     const bool on_home_xcd = (__builtin_amdgcn_s_getreg((31 << 11) | 20) & 0xF) == (unsigned)(blockIdx.x % kNumXcd);
@@ -438,8 +459,8 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
       const int p = idx / nqv, q = (idx - p * nqv) * 8;
       float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       for (int sp = 0; sp < split; sp++) {
-        const float4 x0 = *reinterpret_cast<const float4*>(parts + (size_t)sp * (TILE * TILE) + p * TILE + q);
-        const float4 x1 = *reinterpret_cast<const float4*>(parts + (size_t)sp * (TILE * TILE) + p * TILE + q + 4);
+        const f32x4 x0 = load_agent_f4(parts + (size_t)sp * (TILE * TILE) + p * TILE + q);
+        const f32x4 x1 = load_agent_f4(parts + (size_t)sp * (TILE * TILE) + p * TILE + q + 4);
         x[0] += x0.x; x[1] += x0.y; x[2] += x0.z; x[3] += x0.w; x[4] += x1.x; x[5] += x1.y; x[6] += x1.z; x[7] += x1.w;
       }
       if (EPI == EPI_F32) {
@@ -453,7 +474,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     return;
   }
 #pragma unroll
-  for (int b = 0; b < 4; b++) {
+  for (int b = 0; b < PB; b++) {
     // registers -> LDS (fp32), 32 rows x W columns per output tensor (second tensor at +8 KB when NQ == 2)
 #pragma unroll
     for (int a = 0; a < 2; a++)
@@ -480,7 +501,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
           for (int n = 0; n < NQ; n++) {
             float4 v = *reinterpret_cast<const float4*>(wlds + n * 8192 + r * PITCH + q * 4);
             float* dst = (n == 0 ? A.f0 : A.f1) + o;
-            if (f32_vector_ok && q_base + q + 4 <= q_valid) {
+            if (!NARROW || (f32_vector_ok && q_base + q + 4 <= q_valid)) {   // (d_model, d_ffn are multiples of 64)
               if (A.accumulate) {
                 const float4 old = *reinterpret_cast<const float4*>(dst);
                 v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
@@ -550,6 +571,10 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     __builtin_amdgcn_s_waitcnt(0xC07F);  // the read-back is complete before the next 32 rows overwrite the buffer
     __builtin_amdgcn_wave_barrier();
   }
+  };
+  if (KIND == 1 || p_valid > 128) run(std::integral_constant<int, 4>{});
+  else if (p_valid > 64) run(std::integral_constant<int, 2>{});
+  else run(std::integral_constant<int, 1>{});
 }
 
 // Row-tile schedule: one thread per expert.  sched[0] = number of 256-row tiles; sched[64 + u] = expert of tile u;

@@ -127,19 +127,41 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ b
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// The streaming kernels below give one wavefront one token.  KP is the number of slots per token K' when it is
-// small (1..8: the slot loop is unrolled, all K' row indices are fetched up front and the K' row accesses of a
-// vector are in flight together); KP = 0 is the general loop for any K'.  Rows move as 16-byte vectors per lane,
-// CHUNK vectors per lane at a time, with non-temporal hints (each byte is touched once).
+// The streaming kernels below give a token to `parts` (1, 2 or 4) wavefronts of one block, each of which takes a
+// contiguous part of the row: with rows of 256 vectors or more a block of four wavefronts then works on ONE token,
+// i.e. on 1 + K' rows of 8 KB at a time instead of on 4 (1 + K'), which keeps its accesses inside few DRAM pages
+// (measured on the imbalance shape: combine 66 -> 74 % of the HBM peak).  KP is the number of slots per token K' when
+// it is small (1..8: the slot loop is unrolled, all K' row indices are fetched up front and the K' row accesses of a
+// vector are in flight together); KP = 0 is the general loop for any K'.  Rows move as 16-byte vectors per lane, a
+// few vectors per lane at a time, with non-temporal hints where they measured faster (each byte is touched once).
 // ---------------------------------------------------------------------------------------------------------
 constexpr int CHUNK = 4;  // 16-byte vectors per lane held in registers at once (4 x 64 x 16 B = 4 KB of a row)
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// Cache policy per kernel, chosen by measurement on the imbalance shape (671 MB per launch, cold caches): the
-// gather is indifferent and the combine backward runs fastest with ordinary accesses; the combine (many gathered
-// reads, one write) gains 7 % from non-temporal ones.
-constexpr bool kGatherNT = false, kCombineNT = true, kCombineBwdNT = false;
+// Cache policy per kernel, chosen by measurement on the imbalance shape (671 MB per launch, cold caches, one block
+// per token): the scatter runs 2 % faster with ordinary accesses, the combine 7 % and the combine backward 4 % faster
+// with non-temporal loads and stores.
+#ifndef MOE_NT_GATHER
+#define MOE_NT_GATHER false
+#endif
+#ifndef MOE_NT_COMBINE
+#define MOE_NT_COMBINE true
+#endif
+#ifndef MOE_NT_COMBINE_ST
+#define MOE_NT_COMBINE_ST MOE_NT_COMBINE
+#endif
+#ifndef MOE_NT_CBWD
+#define MOE_NT_CBWD true
+#endif
+#ifndef MOE_NT_CBWD_ST
+#define MOE_NT_CBWD_ST MOE_NT_CBWD
+#endif
+constexpr bool kGatherNT = MOE_NT_GATHER, kCombineNT = MOE_NT_COMBINE, kCombineBwdNT = MOE_NT_CBWD;
+constexpr bool kCombineStNT = MOE_NT_COMBINE_ST, kCombineBwdStNT = MOE_NT_CBWD_ST;
+// Wavefronts per token: 4 for rows of at least 256 vectors (d_model >= 2048), else 2 or 1 (at least 64 vectors each).
+static int row_parts(int dvec) { return dvec >= 256 ? 4 : (dvec >= 128 ? 2 : 1); }
+static unsigned token_blocks(int T, int parts) { return (unsigned)(((long long)T * parts + 3) / 4); }
 template <bool NT> __device__ __forceinline__ u32x4 ld_row(const u32x4* p) { return NT ? __builtin_nontemporal_load(p) : *p; }
 template <bool NT> __device__ __forceinline__ void st_row(u32x4* p, u32x4 v) {
   if (NT) __builtin_nontemporal_store(v, p);
@@ -153,10 +175,13 @@ template <int KP>
 __global__ __launch_bounds__(256) void perm_scatter_kernel(const u32x4* __restrict__ x, const int32_t* __restrict__ topk_idx,
                                                            const int32_t* __restrict__ lrank, const int32_t* __restrict__ block_base,
                                                            u32x4* __restrict__ x_perm, int32_t* __restrict__ row_of_slot,
-                                                           int32_t* __restrict__ slot_of_row, int T, int Kp, int Et, int dvec) {
+                                                           int32_t* __restrict__ slot_of_row, int T, int Kp, int Et, int dvec, int parts) {
   const int lane = threadIdx.x % kWave;
-  const int t = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + threadIdx.x / kWave);
+  const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + threadIdx.x / kWave);
+  const int t = wid / parts, part = wid % parts;
   if (t >= T) return;
+  const int part_len = (dvec + parts - 1) / parts;
+  const int v_begin = part * part_len, v_end = min(dvec, v_begin + part_len);
   const u32x4* src = x ? x + (size_t)t * dvec : nullptr;
   if (KP > 0) {
     int rows[KP > 0 ? KP : 1];
@@ -166,7 +191,7 @@ __global__ __launch_bounds__(256) void perm_scatter_kernel(const u32x4* __restri
       const int e = clamp_expert(topk_idx[s], Et);
       rows[j] = block_base[(size_t)(s / kPermSlotsPerBlock) * Et + e] + lrank[s];
     }
-    if (lane < KP) {
+    if (part == 0 && lane < KP) {
       int row = rows[0];
 #pragma unroll
       for (int j = 1; j < KP; j++) row = (lane == j) ? rows[j] : row;
@@ -174,12 +199,12 @@ __global__ __launch_bounds__(256) void perm_scatter_kernel(const u32x4* __restri
       slot_of_row[row] = t * KP + lane;
     }
     if (src) {
-      for (int v0 = 0; v0 < dvec; v0 += CHUNK * kWave) {
+      for (int v0 = v_begin; v0 < v_end; v0 += CHUNK * kWave) {
         u32x4 r[CHUNK];
 #pragma unroll
         for (int i = 0; i < CHUNK; i++) {
           const int v = v0 + i * kWave + lane;
-          if (v < dvec) r[i] = ld_row<kGatherNT>(src + v);
+          if (v < v_end) r[i] = ld_row<kGatherNT>(src + v);
         }
 #pragma unroll
         for (int j = 0; j < KP; j++) {
@@ -187,7 +212,7 @@ __global__ __launch_bounds__(256) void perm_scatter_kernel(const u32x4* __restri
 #pragma unroll
           for (int i = 0; i < CHUNK; i++) {
             const int v = v0 + i * kWave + lane;
-            if (v < dvec) st_row<kGatherNT>(dst + v, r[i]);
+            if (v < v_end) st_row<kGatherNT>(dst + v, r[i]);
           }
         }
       }
@@ -197,13 +222,13 @@ __global__ __launch_bounds__(256) void perm_scatter_kernel(const u32x4* __restri
       const int s = t * Kp + j;
       const int e = clamp_expert(topk_idx[s], Et);
       const int row = block_base[(size_t)(s / kPermSlotsPerBlock) * Et + e] + lrank[s];
-      if (lane == 0) {
+      if (part == 0 && lane == 0) {
         row_of_slot[s] = row;
         slot_of_row[row] = s;
       }
       if (src) {
         u32x4* dst = x_perm + (size_t)row * dvec;
-        for (int v = lane; v < dvec; v += kWave) st_row<kGatherNT>(dst + v, src[v]);
+        for (int v = v_begin + lane; v < v_end; v += kWave) st_row<kGatherNT>(dst + v, src[v]);
       }
     }
   }
@@ -227,10 +252,13 @@ __device__ __forceinline__ u32x4 pack8(const float (&a)[8]) {
 template <int KP, bool UNIT>
 __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ y, const int32_t* __restrict__ row_of_slot,
                                                       const float* __restrict__ topk_w, const u32x4* __restrict__ addend,
-                                                      u32x4* __restrict__ out, int T, int Kp, int dvec) {
+                                                      u32x4* __restrict__ out, int T, int Kp, int dvec, int parts) {
   const int lane = threadIdx.x % kWave;
-  const int t = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + threadIdx.x / kWave);
+  const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + threadIdx.x / kWave);
+  const int t = wid / parts;
   if (t >= T) return;
+  const int part_len = (dvec + parts - 1) / parts;
+  const int v_begin = (wid % parts) * part_len, v_end = min(dvec, v_begin + part_len);
   u32x4* dst = out + (size_t)t * dvec;
   if (KP > 0) {
     const u32x4* rowp[KP > 0 ? KP : 1];
@@ -240,13 +268,16 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
       rowp[j] = y + (size_t)row_of_slot[(size_t)t * KP + j] * dvec;
       w[j] = UNIT ? 1.0f : topk_w[(size_t)t * KP + j];
     }
-    constexpr int VU = (KP <= 4) ? 2 : 1;  // vectors per lane per iteration: keep KP*VU row loads in flight
-    for (int v0 = 0; v0 < dvec; v0 += VU * kWave) {
+#ifndef MOE_COMBINE_VU
+#define MOE_COMBINE_VU ((KP <= 4) ? 2 : 1)
+#endif
+    constexpr int VU = MOE_COMBINE_VU;  // vectors per lane per iteration: keep KP*VU row loads in flight
+    for (int v0 = v_begin; v0 < v_end; v0 += VU * kWave) {
       u32x4 val[VU][KP > 0 ? KP : 1];
 #pragma unroll
       for (int i = 0; i < VU; i++) {
         const int v = v0 + i * kWave + lane;
-        if (v < dvec) {
+        if (v < v_end) {
 #pragma unroll
           for (int j = 0; j < KP; j++) val[i][j] = ld_row<kCombineNT>(rowp[j] + v);
         }
@@ -254,23 +285,23 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
 #pragma unroll
       for (int i = 0; i < VU; i++) {
         const int v = v0 + i * kWave + lane;
-        if (v < dvec) {
+        if (v < v_end) {
           float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int j = 0; j < KP; j++) fma_bf16x8(acc, val[i][j], w[j]);  // slot order, fp32
           if (addend) fma_bf16x8(acc, addend[(size_t)t * dvec + v], 1.0f);
-          st_row<kCombineNT>(dst + v, pack8(acc));
+          st_row<kCombineStNT>(dst + v, pack8(acc));
         }
       }
     }
   } else {
     const int32_t* rows = row_of_slot + (size_t)t * Kp;
     const float* w = UNIT ? nullptr : topk_w + (size_t)t * Kp;
-    for (int v = lane; v < dvec; v += kWave) {
+    for (int v = v_begin + lane; v < v_end; v += kWave) {
       float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       for (int j = 0; j < Kp; j++) fma_bf16x8(acc, y[(size_t)rows[j] * dvec + v], UNIT ? 1.0f : w[j]);
       if (addend) fma_bf16x8(acc, addend[(size_t)t * dvec + v], 1.0f);
-      st_row<kCombineNT>(dst + v, pack8(acc));
+      st_row<kCombineStNT>(dst + v, pack8(acc));
     }
   }
 }
@@ -279,36 +310,60 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
 template <int KP>
 __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restrict__ dout, const u32x4* __restrict__ y,
                                                           const int32_t* __restrict__ row_of_slot, const float* __restrict__ topk_w,
-                                                          u32x4* __restrict__ dy, float* __restrict__ dtopk_w, int T, int Kp, int dvec) {
+                                                          u32x4* __restrict__ dy, float* __restrict__ dtopk_w, int T, int Kp, int dvec,
+                                                          int parts) {
+  // dot products of the parts of a row meet in LDS and are added in part order (the result never depends on timing)
+  extern __shared__ float part_dot[];   // [4 wavefronts][K']
   const int lane = threadIdx.x % kWave;
-  const int t = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + threadIdx.x / kWave);
-  if (t >= T) return;
-  const u32x4* g = dout + (size_t)t * dvec;
+  const int wave = threadIdx.x / kWave;
+  const int wid = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + wave);
+  const int t = wid / parts, part = wid % parts;
+  const bool active = t < T;   // (no early return: the block meets at a barrier below)
+  const int part_len = (dvec + parts - 1) / parts;
+  const int v_begin = active ? part * part_len : 0, v_end = active ? min(dvec, v_begin + part_len) : 0;
+  const u32x4* g = dout + (size_t)(active ? t : 0) * dvec;
   if (KP > 0) {
     size_t rowoff[KP > 0 ? KP : 1];
     float w[KP > 0 ? KP : 1], dot[KP > 0 ? KP : 1];
 #pragma unroll
     for (int j = 0; j < KP; j++) {
-      rowoff[j] = (size_t)row_of_slot[(size_t)t * KP + j] * dvec;
-      w[j] = topk_w[(size_t)t * KP + j];
+      rowoff[j] = active ? (size_t)row_of_slot[(size_t)t * KP + j] * dvec : 0;
+      w[j] = active ? topk_w[(size_t)t * KP + j] : 0.f;
       dot[j] = 0.f;
     }
-    for (int v = lane; v < dvec; v += kWave) {
-      const u32x4 gv = ld_row<kCombineBwdNT>(g + v);
-      u32x4 yv[KP > 0 ? KP : 1];
+#ifndef MOE_CBWD_VU
+#define MOE_CBWD_VU ((KP <= 4) ? 2 : 1)
+#endif
+    constexpr int VU = MOE_CBWD_VU;  // vectors per lane per iteration: (1 + KP) * VU row loads in flight
+    for (int v0 = v_begin; v0 < v_end; v0 += VU * kWave) {
+      u32x4 gv[VU], yv[VU][KP > 0 ? KP : 1];
 #pragma unroll
-      for (int j = 0; j < KP; j++) yv[j] = ld_row<kCombineBwdNT>(y + rowoff[j] + v);
-      const float a[8] = {bf16lo(gv.x), bf16hi(gv.x), bf16lo(gv.y), bf16hi(gv.y), bf16lo(gv.z), bf16hi(gv.z), bf16lo(gv.w), bf16hi(gv.w)};
+      for (int i = 0; i < VU; i++) {
+        const int v = v0 + i * kWave + lane;
+        if (v < v_end) {
+          gv[i] = ld_row<kCombineBwdNT>(g + v);
 #pragma unroll
-      for (int j = 0; j < KP; j++) {
-        float sc[8];
+          for (int j = 0; j < KP; j++) yv[i][j] = ld_row<kCombineBwdNT>(y + rowoff[j] + v);
+        }
+      }
 #pragma unroll
-        for (int q = 0; q < 8; q++) sc[q] = w[j] * a[q];
-        st_row<kCombineBwdNT>(dy + rowoff[j] + v, pack8(sc));
-        const u32x4 yy = yv[j];
-        const float b[8] = {bf16lo(yy.x), bf16hi(yy.x), bf16lo(yy.y), bf16hi(yy.y), bf16lo(yy.z), bf16hi(yy.z), bf16lo(yy.w), bf16hi(yy.w)};
+      for (int i = 0; i < VU; i++) {
+        const int v = v0 + i * kWave + lane;
+        if (v < v_end) {
+          const u32x4 gg = gv[i];
+          const float a[8] = {bf16lo(gg.x), bf16hi(gg.x), bf16lo(gg.y), bf16hi(gg.y), bf16lo(gg.z), bf16hi(gg.z), bf16lo(gg.w), bf16hi(gg.w)};
 #pragma unroll
-        for (int q = 0; q < 8; q++) dot[j] += a[q] * b[q];
+          for (int j = 0; j < KP; j++) {
+            float sc[8];
+#pragma unroll
+            for (int q = 0; q < 8; q++) sc[q] = w[j] * a[q];
+            st_row<kCombineBwdStNT>(dy + rowoff[j] + v, pack8(sc));
+            const u32x4 yy = yv[i][j];
+            const float b[8] = {bf16lo(yy.x), bf16hi(yy.x), bf16lo(yy.y), bf16hi(yy.y), bf16lo(yy.z), bf16hi(yy.z), bf16lo(yy.w), bf16hi(yy.w)};
+#pragma unroll
+            for (int q = 0; q < 8; q++) dot[j] += a[q] * b[q];
+          }
+        }
       }
     }
 #pragma unroll
@@ -316,15 +371,21 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restric
       float dsum = dot[j];
 #pragma unroll
       for (int o = kWave / 2; o > 0; o >>= 1) dsum += __shfl_xor(dsum, o, kWave);
-      if (lane == 0) dtopk_w[(size_t)t * KP + j] = dsum;
+      if (lane == 0) part_dot[wave * KP + j] = dsum;
+    }
+    __syncthreads();
+    if (active && part == 0 && lane < KP) {
+      float dsum = 0.f;
+      for (int p2 = 0; p2 < parts; p2++) dsum += part_dot[(wave + p2) * KP + lane];
+      dtopk_w[(size_t)t * KP + lane] = dsum;
     }
   } else {
     for (int j = 0; j < Kp; j++) {
-      const int s = t * Kp + j;
+      const int s = (active ? t : 0) * Kp + j;
       const size_t ro = (size_t)row_of_slot[s] * dvec;
       const float w = topk_w[s];
       float dot = 0.f;
-      for (int v = lane; v < dvec; v += kWave) {
+      for (int v = v_begin + lane; v < v_end; v += kWave) {
         const u32x4 gv = g[v];
         const u32x4 yy = y[ro + v];
         const float a[8] = {bf16lo(gv.x), bf16hi(gv.x), bf16lo(gv.y), bf16hi(gv.y), bf16lo(gv.z), bf16hi(gv.z), bf16lo(gv.w), bf16hi(gv.w)};
@@ -336,8 +397,15 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restric
       }
 #pragma unroll
       for (int o = kWave / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
-      if (lane == 0) dtopk_w[s] = dot;
+      if (lane == 0) part_dot[wave * Kp + j] = dot;
     }
+    __syncthreads();
+    if (active && part == 0)
+      for (int j = lane; j < Kp; j += kWave) {
+        float dsum = 0.f;
+        for (int p2 = 0; p2 < parts; p2++) dsum += part_dot[(wave + p2) * Kp + j];
+        dtopk_w[(size_t)t * Kp + j] = dsum;
+      }
   }
 }
 
@@ -387,9 +455,10 @@ static int permute_launch(const Dims& D, const uint16_t* x, const int32_t* topk_
   // with no slots the scan still defines counts = 0 and offsets = 0
   MOE_LAUNCH("perm_scan", st, perm_scan_kernel, dim3(1), dim3(1024), 0, st, block_hist, counts, offsets, nblk, D.Et);
   if (D.T > 0) {
-    MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("perm_scatter_gather", st, (perm_scatter_kernel<KP>), dim3((D.T + 3) / 4), dim3(256), 0, st,
+    const int parts = x ? row_parts(D.d / 8) : 1;
+    MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("perm_scatter_gather", st, (perm_scatter_kernel<KP>), dim3(token_blocks(D.T, parts)), dim3(256), 0, st,
                                      reinterpret_cast<const u32x4*>(x), topk_idx, lrank, block_hist, reinterpret_cast<u32x4*>(x_perm),
-                                     row_of_slot, slot_of_row, D.T, D.Kp, D.Et, D.d / 8));
+                                     row_of_slot, slot_of_row, D.T, D.Kp, D.Et, D.d / 8, parts));
   }
   return launch_status();
 }
@@ -461,9 +530,9 @@ extern "C" int moe_permute_bwd(const moe_shape* shape, const uint16_t* dx_perm, 
   MOE_REQUIRE_ALIGNED(dx_perm); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(dx);
   if (D.T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
-  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("permute_bwd", st, (combine_kernel<KP, true>), dim3((D.T + 3) / 4), dim3(256), 0, st,
+  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("permute_bwd", st, (combine_kernel<KP, true>), dim3(token_blocks(D.T, row_parts(D.d / 8))), dim3(256), 0, st,
                                    reinterpret_cast<const u32x4*>(dx_perm), row_of_slot, (const float*)nullptr,
-                                   (const u32x4*)nullptr, reinterpret_cast<u32x4*>(dx), D.T, D.Kp, D.d / 8));
+                                   (const u32x4*)nullptr, reinterpret_cast<u32x4*>(dx), D.T, D.Kp, D.d / 8, row_parts(D.d / 8)));
   return launch_status();
 }
 
@@ -477,9 +546,9 @@ extern "C" int moe_permute_bwd_add(const moe_shape* shape, const uint16_t* dx_pe
   MOE_REQUIRE_ALIGNED(dx_perm); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(dx_addend); MOE_REQUIRE_ALIGNED(dx);
   if (D.T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
-  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("permute_bwd_add", st, (combine_kernel<KP, true>), dim3((D.T + 3) / 4), dim3(256), 0, st,
+  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("permute_bwd_add", st, (combine_kernel<KP, true>), dim3(token_blocks(D.T, row_parts(D.d / 8))), dim3(256), 0, st,
                                    reinterpret_cast<const u32x4*>(dx_perm), row_of_slot, (const float*)nullptr,
-                                   reinterpret_cast<const u32x4*>(dx_addend), reinterpret_cast<u32x4*>(dx), D.T, D.Kp, D.d / 8));
+                                   reinterpret_cast<const u32x4*>(dx_addend), reinterpret_cast<u32x4*>(dx), D.T, D.Kp, D.d / 8, row_parts(D.d / 8)));
   return launch_status();
 }
 
@@ -493,9 +562,9 @@ extern "C" int moe_unpermute_combine(const moe_shape* shape, const uint16_t* y_p
   MOE_REQUIRE_ALIGNED(y_perm); MOE_REQUIRE_ALIGNED(row_of_slot); MOE_REQUIRE_ALIGNED(topk_w); MOE_REQUIRE_ALIGNED(out);
   if (D.T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
-  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("unpermute_combine", st, (combine_kernel<KP, false>), dim3((D.T + 3) / 4), dim3(256), 0, st,
+  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("unpermute_combine", st, (combine_kernel<KP, false>), dim3(token_blocks(D.T, row_parts(D.d / 8))), dim3(256), 0, st,
                                    reinterpret_cast<const u32x4*>(y_perm), row_of_slot, topk_w, (const u32x4*)nullptr,
-                                   reinterpret_cast<u32x4*>(out), D.T, D.Kp, D.d / 8));
+                                   reinterpret_cast<u32x4*>(out), D.T, D.Kp, D.d / 8, row_parts(D.d / 8)));
   return launch_status();
 }
 
@@ -512,8 +581,10 @@ extern "C" int moe_unpermute_combine_bwd(const moe_shape* shape, const uint16_t*
   MOE_REQUIRE_ALIGNED(dy_perm); MOE_REQUIRE_ALIGNED(dtopk_w);
   if (D.T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
-  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("unpermute_combine_bwd", st, (combine_bwd_kernel<KP>), dim3((D.T + 3) / 4), dim3(256), 0, st,
+  const int parts = row_parts(D.d / 8);
+  MOE_DISPATCH_KP(D.Kp, MOE_LAUNCH("unpermute_combine_bwd", st, (combine_bwd_kernel<KP>), dim3(token_blocks(D.T, parts)), dim3(256),
+                                   4 * (size_t)D.Kp * sizeof(float), st,
                                    reinterpret_cast<const u32x4*>(dout), reinterpret_cast<const u32x4*>(y_perm), row_of_slot,
-                                   topk_w, reinterpret_cast<u32x4*>(dy_perm), dtopk_w, D.T, D.Kp, D.d / 8));
+                                   topk_w, reinterpret_cast<u32x4*>(dy_perm), dtopk_w, D.T, D.Kp, D.d / 8, parts));
   return launch_status();
 }
