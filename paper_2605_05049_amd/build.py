@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_NAME = "libmoe_gfx950.so"
 LIB_PATH = os.path.join(PKG_DIR, LIB_NAME)
-SOURCES = ["api.hip", "route.hip", "permute.hip", "grouped_gemm.hip", "rebalance.hip", "halo.hip"]
+SOURCES = ["api.hip", "route.hip", "router.hip", "permute.hip", "grouped_gemm.hip", "rebalance.hip", "halo.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 math is switched off on purpose (the compiler would otherwise form it from plain float code)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

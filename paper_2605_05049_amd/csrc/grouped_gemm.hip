@@ -454,7 +454,6 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     // the valid part of the tile only: p_valid rows of ceil(q_valid / 8) groups of 8 columns, spread over all threads
     const int nqv = (q_valid + 7) >> 3;
     const int n_items = p_valid * nqv;
-#pragma unroll 2
     for (int idx = tid; idx < n_items; idx += NTHREADS) {
       const int p = idx / nqv, q = (idx - p * nqv) * 8;
       float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -774,40 +773,6 @@ extern "C" int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_pe
   A.q0 = dg; A.q1 = du; A.q_ld = D.f;
   A.f0 = dw_gate; A.f1 = dw_up; A.f_expert_stride = (size_t)D.d * D.f; A.c_ld = D.f;
   MOE_TRY((launch_gemm<1, true, true, 2, 1, EPI_F32>("ffn_bwd_dw_gate_up", A, wgrad_blocks(D.Et, A.n_p_tiles, A.n_q_tiles), st)));
-  return launch_status();
-}
-
-extern "C" int moe_router_fwd(const moe_shape* shape, const uint16_t* x, const uint16_t* w_router, float* logits,
-                              void* ws, size_t ws_bytes, void* stream) {
-  using namespace moe;
-  Dims D;
-  WsLayout L;
-  int rc = common_checks(shape, &D, ws, ws_bytes, &L);
-  if (rc != MOE_OK) return rc;
-  MOE_REQUIRE_PTR(x); MOE_REQUIRE_PTR(w_router); MOE_REQUIRE_PTR(logits);
-  MOE_REQUIRE_ALIGNED(x); MOE_REQUIRE_ALIGNED(w_router); MOE_REQUIRE_ALIGNED(logits);
-  if (D.T == 0) return MOE_OK;
-  hipStream_t st = (hipStream_t)stream;
-  char* wsb = static_cast<char*>(ws);
-  int32_t* sched = reinterpret_cast<int32_t*>(wsb + L.sched);
-  uint32_t* zero_page = reinterpret_cast<uint32_t*>(wsb + L.zero_page);
-  int32_t* counters = reinterpret_cast<int32_t*>(wsb + L.splitk_counters);
-  int32_t* offs = reinterpret_cast<int32_t*>(wsb + L.router_offsets);
-  const int max_tiles = (int)sched_max_tiles(D);
-  MOE_LAUNCH("router_prepare", st, router_prepare_kernel, dim3(1), dim3(256), 0, st, (const float*)nullptr, (uint16_t*)nullptr,
-             (uint16_t*)nullptr, offs, (int)D.T, (int)D.E, 0);
-  MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs, sched, zero_page, counters, 1, max_tiles);
-  GemmArgs A = {};
-  A.sched = sched; A.max_tiles = max_tiles; A.offsets = offs; A.Et = 1;
-  A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
-  A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
-  // logits[T,E] = X W_r^T: rows = tokens, columns = experts, K = d; both operands K-contiguous
-  A.n_q_tiles = (D.E + TILE - 1) / TILE; A.q_dim = D.E; A.k_dim = D.d;
-  A.p0 = x; A.p_ld = D.d;
-  A.q0 = w_router; A.q_ld = D.d; A.q_expert_stride = 0;
-  A.f0 = logits; A.f_expert_stride = 0; A.c_ld = D.E;
-  const long long row_tiles = (D.T + TILE - 1) / TILE;
-  MOE_TRY((launch_gemm<0, false, false, 1, 1, EPI_F32>("router_fwd", A, row_tiles * A.n_q_tiles, st)));
   return launch_status();
 }
 
