@@ -6,8 +6,10 @@ batch of seeded synthetic input already resident in HBM.
 Prints ONE JSON line.  `value` is fwd+bwd TFLOP/s with FLOPs = 18*d*f*N (three 2*d*f GEMMs per permuted row forward,
 twice that backward; padded rows and empty experts are never counted).  `roofline` prices the slowest kernel of the
 step against the bf16 dense MFMA peak from per-launch HIP-event timings taken live in a second, instrumented pass.
-`permute_combine` reports the streaming kernels' HBM rate on the imbalance workload.  `cpu_baseline` times the fp64
-oracle on a bounded sample of the same workload on the host cores.
+`permute_combine` reports the streaming kernels' HBM rate on the imbalance workload, `workloads` the same step on the
+other three full-size workloads (each GEMM priced against the larger of its MFMA and its HBM time), `calibration` what
+plain device copies, fills and reductions reach on the same box.  `cpu_baseline` times the fp64 oracle on a bounded
+sample of the same workload on the host cores.
 """
 from __future__ import annotations
 
@@ -24,10 +26,29 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E, published
 
-# HBM-side bytes per launch (read + written) of the grouped GEMM kernels on the mixtral workload, from the rocprofv3
-# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/grouped_gemm_mixtral_hbm_traffic.txt (scaled by the plain-copy
-# calibration of the same runs).  Counters cannot be read from inside this script; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {"mixtral": {"ffn_bwd_dx": 3854146862, "ffn_bwd_dw_gate_up": 6577116271, "ffn_fwd_gate_up_swiglu": 4658355365, "ffn_fwd_down": 1942290528, "ffn_bwd_dw_down": 3289370786, "ffn_bwd_dh_dswiglu": 3220287860}}
+PROFILE_DIR = os.path.join(ROOT, "profiles")
+
+
+def measured_traffic_bytes(workload):
+    """HBM-side bytes per launch (read + written) of the grouped GEMM kernels, from the committed summary of the two
+    rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE in KiB per dispatch, each scaled by what the same counter read for a
+    plain copy of known size): profiles/grouped_gemm_<workload>_hbm_traffic.txt.  Counters cannot be read from inside
+    this script; a workload without such a summary reports null."""
+    path = os.path.join(PROFILE_DIR, f"grouped_gemm_{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return {}
+    import re
+    text = open(path).read()
+    m = re.search(r"scale factors ([0-9.]+) \(fetch\), ([0-9.]+) \(write\)", text)
+    if not m:
+        return {}
+    sf, sw = float(m.group(1)), float(m.group(2))
+    out = {}
+    for line in text.splitlines():
+        f = line.split()
+        if len(f) == 8 and f[0].startswith("ffn_"):
+            out[f[0]] = int((float(f[1]) * sf + float(f[4]) * sw) * 1024)
+    return out
 
 
 def parse_args():
@@ -39,8 +60,10 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-streaming", action="store_true", help="skip the permute/combine bandwidth measurement")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 512 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--no-calibration", action="store_true",
+                    help="skip the plain 512 MiB device copy / fill / reduction (what this box's HBM reaches; the copy is also "
+                         "the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the brief runs of the other full-size workloads")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens of the workload the oracle is timed on (0 = auto)")
     return ap.parse_args()
 
@@ -56,6 +79,28 @@ def gemm_flops_per_launch(label, shape):
     unit = 2.0 * shape.d_model * shape.d_ffn * shape.N
     return {"ffn_fwd_gate_up_swiglu": 2 * unit, "ffn_fwd_down": unit, "ffn_bwd_dh_dswiglu": unit,
             "ffn_bwd_dx": 2 * unit, "ffn_bwd_dw_down": unit, "ffn_bwd_dw_gate_up": 2 * unit}.get(label)
+
+
+def gemm_bytes_per_launch(label, shape, n_active):
+    """Algorithmic HBM bytes of one launch of each grouped-GEMM kernel: every operand read once, every output written
+    once; weights only of the n_active experts that have rows; the fp32 weight gradients of all E' experts (empty ones
+    are zero-filled)."""
+    d, f, N, Et = shape.d_model, shape.d_ffn, shape.N, shape.E_total
+    act_d, act_f, w1 = N * d * 2, N * f * 2, n_active * d * f * 2
+    return {"ffn_fwd_gate_up_swiglu": act_d + 2 * w1 + 3 * act_f, "ffn_fwd_down": act_f + w1 + act_d,
+            "ffn_bwd_dh_dswiglu": act_d + w1 + 2 * act_f + 3 * act_f, "ffn_bwd_dx": 2 * act_f + 2 * w1 + act_d,
+            "ffn_bwd_dw_down": act_f + act_d + Et * d * f * 4, "ffn_bwd_dw_gate_up": act_d + 2 * act_f + 2 * Et * d * f * 4}.get(label)
+
+
+def gemm_roofline(label, shape, n_active, avg_ms):
+    """A GEMM launch against the larger of its two lower bounds: FLOPs at the dense bf16 MFMA peak, algorithmic bytes
+    at the HBM peak."""
+    fl, by = gemm_flops_per_launch(label, shape), gemm_bytes_per_launch(label, shape, n_active)
+    t_mfma, t_hbm = fl / (PEAK_BF16_MFMA_TFLOPS * 1e12), by / (PEAK_HBM_GBS * 1e9)
+    t = avg_ms * 1e-3
+    if t_hbm > t_mfma:
+        return {"bound": "hbm", "achieved": round(by / t / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(t_hbm / t, 4)}
+    return {"bound": "mfma", "achieved": round(fl / t / 1e12, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(t_mfma / t, 4)}
 
 
 def stream_bytes_per_launch(label, shape):
@@ -132,7 +177,81 @@ def run_layer_bench(moe, W, args):
     for name, ms in recs:
         per_kernel.setdefault(name, []).append(ms)
     kernels = {k: {"launches_per_step": len(v) // prof_steps, "avg_ms": sum(v) / len(v)} for k, v in per_kernel.items()}
-    return inp, sh, elapsed, kernels, gen_s, split
+    counts = buf.counts.cpu().numpy()
+    load = {"experts_with_rows": int((counts > 0).sum()), "rows_min": int(counts.min()), "rows_median": int(sorted(counts)[len(counts) // 2]),
+            "rows_max": int(counts.max())}
+    return inp, sh, elapsed, kernels, gen_s, split, load
+
+
+def run_workload_brief(moe, W, name, steps, seed):
+    """One of the other full-size workloads, briefly: the same whole step (route -> ... -> route_bwd) on the workload's
+    own routing input and seeded tokens; the expert weights are drawn on the device (N(0, 0.02), bf16) instead of on the
+    host to keep the run short.  Reports ms per step, TFLOP/s and every GEMM against its own bound."""
+    import torch
+    wl = W.WORKLOADS[name]
+    sh = wl.shape
+    inp = W.make_layer_inputs(wl, seed=seed, with_weights=False)
+    s = moe.Shape.of(sh)
+    buf = moe.MoeLayerBuffers(s)
+    x, dout = dev_bf16(inp["x"]), dev_bf16(inp["dout"])
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    Et, d, f = sh.E_total, sh.d_model, sh.d_ffn
+    wg = (torch.randn((Et, d, f), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    wu = (torch.randn((Et, d, f), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    wd = (torch.randn((Et, f, d), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    if "logits" in inp:
+        logits = torch.from_numpy(inp["logits"]).cuda()
+    else:
+        logits = None
+        buf.topk_idx.copy_(torch.from_numpy(inp["topk_idx"]).cuda())
+        buf.topk_w.copy_(torch.from_numpy(inp["topk_w"]).cuda())
+
+    def step():
+        moe.layer_forward(buf, x, wg, wu, wd, logits)
+        moe.layer_backward(buf, dout, wg, wu, wd, accumulate=False, with_router=logits is not None)
+
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    e1.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    moe.profile_reset()
+    moe.profile_enable(True)
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    moe.profile_enable(False)
+    per = {}
+    for kn, t in moe.profile_records():
+        per.setdefault(kn, []).append(t)
+    moe.profile_reset()
+    counts = buf.counts.cpu().numpy()
+    n_active = int((counts > 0).sum())
+    gemms, t_bound = {}, 0.0
+    for kn, v in per.items():
+        if gemm_flops_per_launch(kn, sh):
+            avg = sum(v) / len(v)
+            r = gemm_roofline(kn, sh, n_active, avg)
+            gemms[kn] = {"avg_ms": round(avg, 4), "bound": r["bound"], "frac": r["frac"]}
+            t_bound += r["frac"] * avg
+    dom = max(gemms, key=lambda k: gemms[k]["avg_ms"])
+    flops = sh.flops_fwd_bwd()
+    out = {"config": f"T={sh.T} d_model={sh.d_model} d_ffn={sh.d_ffn} E={sh.E}+{sh.E_shared} shared top-{sh.k} (N={sh.N} rows)",
+           "ms_per_step": round(ms, 4), "TFLOPs": round(flops / (ms * 1e-3) / 1e12, 1),
+           "frac_bf16_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
+           "gemm_ms": round(sum(e["avg_ms"] for e in gemms.values()), 4),
+           "gemm_frac_of_own_bounds": round(t_bound / sum(e["avg_ms"] for e in gemms.values()), 4),
+           "dominant": dict(kernel=dom, **gemms[dom]), "gemms": gemms,
+           "rows_per_expert": {"with_rows": n_active, "min": int(counts.min()), "median": int(sorted(counts)[len(counts) // 2]), "max": int(counts.max())}}
+    del buf, wg, wu, wd
+    torch.cuda.empty_cache()
+    return out
 
 
 def run_streaming_bench(moe, W, steps):
@@ -198,10 +317,19 @@ def run_streaming_bench(moe, W, steps):
                 ent["frac_hbm_peak"] = round(b / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
             out["kernels"][name] = ent
         if call == "moe_permute":
-            tot = sum(sum(v) / len(v) for v in per.values())
+            # the whole call (its three launches back to back, nothing recorded between them): one pair of events around
+            # a run of calls on rotating buffers
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(steps):
+                fn(sets[i % 3])
+            e1.record()
+            e1.synchronize()
+            tot = e0.elapsed_time(e1) / steps
             b = stream_bytes_per_launch("perm_scatter_gather", sh)
             out["moe_permute_total"] = {"avg_us": round(tot * 1e3, 2), "GBs": round(b / (tot * 1e-3) / 1e9, 1),
-                                        "frac_hbm_peak": round(b / (tot * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+                                        "frac_hbm_peak": round(b / (tot * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                        "sum_of_launches_us": round(sum(sum(v) / len(v) for v in per.values()) * 1e3, 2)}
     del sets
     torch.cuda.empty_cache()
     return out
@@ -327,23 +455,32 @@ def run_halo_bench(moe, steps):
     return out
 
 
-def run_copy_calibration():
-    """A plain device-to-device copy of known size (512 MiB read + 512 MiB written per launch, 5 launches): the yard
-    stick the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by."""
+def run_calibration():
+    """What plain streaming reaches on this machine (torch is only the allocator here, but its copy and fill are the simplest
+    yard sticks at hand): a 512 MiB device-to-device copy (also the
+    reference the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by) and a 512 MiB fill (write
+    only), each 5 launches."""
     import torch
     n = 512 * 1024 * 1024
     a = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
     b = torch.empty_like(a)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(5):
-        b.copy_(a)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / 5
-    return {"bytes_read": n, "bytes_written": n, "launches": 5, "avg_us": round(ms * 1e3, 1),
-            "GBs_read_plus_write": round(2 * n / (ms * 1e-3) / 1e9, 1)}
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / 5
+    t_copy, t_fill = timed(lambda: b.copy_(a)), timed(lambda: b.fill_(1))
+    gbs = lambda nbytes, ms: round(nbytes / (ms * 1e-3) / 1e9, 1)  # noqa: E731
+    return {"bytes": n, "launches": 5,
+            "copy": {"avg_us": round(t_copy * 1e3, 1), "GBs_read_plus_write": gbs(2 * n, t_copy), "frac_hbm_peak": round(gbs(2 * n, t_copy) / PEAK_HBM_GBS, 4)},
+            "fill": {"avg_us": round(t_fill * 1e3, 1), "GBs_written": gbs(n, t_fill), "frac_hbm_peak": round(gbs(n, t_fill) / PEAK_HBM_GBS, 4)}}
 
 
 def run_cpu_baseline(W, inp, sh, sample_tokens):
@@ -390,7 +527,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
-    inp, sh, elapsed, kernels, gen_s, split = run_layer_bench(moe, W, args)
+    inp, sh, elapsed, kernels, gen_s, split, load = run_layer_bench(moe, W, args)
     flops = sh.flops_fwd_bwd()
     ms_per_step = elapsed / args.steps * 1e3
     tflops = flops / (ms_per_step * 1e-3) / 1e12
@@ -399,11 +536,10 @@ def main():
     dom = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches_per_step"])
     dom_flops = gemm_flops_per_launch(dom, sh)
     if dom_flops:
-        ach = dom_flops / (kernels[dom]["avg_ms"] * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dom), "kernel": dom,
-                    "avg_ms": round(kernels[dom]["avg_ms"], 4), "flops_per_launch": dom_flops}
+        roofline = gemm_roofline(dom, sh, load["experts_with_rows"], kernels[dom]["avg_ms"])
+        roofline.update({"traffic": measured_traffic_bytes(args.workload).get(dom), "kernel": dom,
+                         "avg_ms": round(kernels[dom]["avg_ms"], 4), "flops_per_launch": dom_flops,
+                         "bytes_per_launch": gemm_bytes_per_launch(dom, sh, load["experts_with_rows"])})
     else:
         b = stream_bytes_per_launch(dom, sh) or 0
         ach = b / (kernels[dom]["avg_ms"] * 1e-3) / 1e9
@@ -417,6 +553,8 @@ def main():
         if fl:
             ent["TFLOPs"] = round(fl / (v["avg_ms"] * 1e-3) / 1e12, 1)
             ent["frac_mfma_peak"] = round(ent["TFLOPs"] / PEAK_BF16_MFMA_TFLOPS, 4)
+            r = gemm_roofline(k, sh, load["experts_with_rows"], v["avg_ms"])
+            ent["bound"], ent["frac_of_bound"] = r["bound"], r["frac"]
         kern_out[k] = ent
 
     res = {
@@ -428,6 +566,7 @@ def main():
                    "flops_per_step": flops},
         "frac_bf16_mfma_peak": round(tflops / PEAK_BF16_MFMA_TFLOPS, 4),
         "roofline": roofline,
+        "rows_per_expert": load,
         "phases": split,
         "kernels": kern_out,
     }
@@ -438,8 +577,13 @@ def main():
     if not args.no_streaming and args.workload == "mixtral":
         res["halo_pack"] = run_halo_bench(moe, steps=10)
         res["graph_replay"] = run_graph_bench(moe, W, steps=200)
-    if args.copy_calibration:
-        res["copy_calibration"] = run_copy_calibration()
+    if not args.no_streaming and args.workload == "mixtral":
+        res["router_imbalance"] = run_router_bench(moe, W, "imbalance", steps=20)
+    if not args.no_workloads and args.workload == "mixtral":
+        res["workloads"] = {name: run_workload_brief(moe, W, name, steps=5, seed=args.seed)
+                            for name in ("finegrained", "shard", "imbalance")}
+    if not args.no_calibration:
+        res["calibration"] = run_calibration()
     if not args.no_cpu_baseline:
         n = args.cpu_sample_tokens
         if n <= 0:

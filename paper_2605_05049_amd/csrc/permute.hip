@@ -142,23 +142,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 // Cache policy per kernel, chosen by measurement on the imbalance shape (671 MB per launch, cold caches, one block
 // per token): the scatter runs 2 % faster with ordinary accesses, the combine 7 % and the combine backward 4 % faster
 // with non-temporal loads and stores.
-#ifndef MOE_NT_GATHER
-#define MOE_NT_GATHER false
-#endif
-#ifndef MOE_NT_COMBINE
-#define MOE_NT_COMBINE true
-#endif
-#ifndef MOE_NT_COMBINE_ST
-#define MOE_NT_COMBINE_ST MOE_NT_COMBINE
-#endif
-#ifndef MOE_NT_CBWD
-#define MOE_NT_CBWD true
-#endif
-#ifndef MOE_NT_CBWD_ST
-#define MOE_NT_CBWD_ST MOE_NT_CBWD
-#endif
-constexpr bool kGatherNT = MOE_NT_GATHER, kCombineNT = MOE_NT_COMBINE, kCombineBwdNT = MOE_NT_CBWD;
-constexpr bool kCombineStNT = MOE_NT_COMBINE_ST, kCombineBwdStNT = MOE_NT_CBWD_ST;
+constexpr bool kGatherNT = false, kCombineNT = true, kCombineBwdNT = true;
 // Wavefronts per token: 4 for rows of at least 256 vectors (d_model >= 2048), else 2 or 1 (at least 64 vectors each).
 static int row_parts(int dvec) { return dvec >= 256 ? 4 : (dvec >= 128 ? 2 : 1); }
 static unsigned token_blocks(int T, int parts) { return (unsigned)(((long long)T * parts + 3) / 4); }
@@ -268,10 +252,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
       rowp[j] = y + (size_t)row_of_slot[(size_t)t * KP + j] * dvec;
       w[j] = UNIT ? 1.0f : topk_w[(size_t)t * KP + j];
     }
-#ifndef MOE_COMBINE_VU
-#define MOE_COMBINE_VU ((KP <= 4) ? 2 : 1)
-#endif
-    constexpr int VU = MOE_COMBINE_VU;  // vectors per lane per iteration: keep KP*VU row loads in flight
+    constexpr int VU = (KP <= 4) ? 2 : 1;  // vectors per lane per iteration: keep KP*VU row loads in flight
     for (int v0 = v_begin; v0 < v_end; v0 += VU * kWave) {
       u32x4 val[VU][KP > 0 ? KP : 1];
 #pragma unroll
@@ -290,7 +271,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
 #pragma unroll
           for (int j = 0; j < KP; j++) fma_bf16x8(acc, val[i][j], w[j]);  // slot order, fp32
           if (addend) fma_bf16x8(acc, addend[(size_t)t * dvec + v], 1.0f);
-          st_row<kCombineStNT>(dst + v, pack8(acc));
+          st_row<kCombineNT>(dst + v, pack8(acc));
         }
       }
     }
@@ -301,7 +282,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
       float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       for (int j = 0; j < Kp; j++) fma_bf16x8(acc, y[(size_t)rows[j] * dvec + v], UNIT ? 1.0f : w[j]);
       if (addend) fma_bf16x8(acc, addend[(size_t)t * dvec + v], 1.0f);
-      st_row<kCombineStNT>(dst + v, pack8(acc));
+      st_row<kCombineNT>(dst + v, pack8(acc));
     }
   }
 }
@@ -331,10 +312,7 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restric
       w[j] = active ? topk_w[(size_t)t * KP + j] : 0.f;
       dot[j] = 0.f;
     }
-#ifndef MOE_CBWD_VU
-#define MOE_CBWD_VU ((KP <= 4) ? 2 : 1)
-#endif
-    constexpr int VU = MOE_CBWD_VU;  // vectors per lane per iteration: (1 + KP) * VU row loads in flight
+    constexpr int VU = (KP <= 4) ? 2 : 1;  // vectors per lane per iteration: (1 + KP) * VU row loads in flight
     for (int v0 = v_begin; v0 < v_end; v0 += VU * kWave) {
       u32x4 gv[VU], yv[VU][KP > 0 ? KP : 1];
 #pragma unroll
@@ -357,7 +335,7 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restric
             float sc[8];
 #pragma unroll
             for (int q = 0; q < 8; q++) sc[q] = w[j] * a[q];
-            st_row<kCombineBwdStNT>(dy + rowoff[j] + v, pack8(sc));
+            st_row<kCombineBwdNT>(dy + rowoff[j] + v, pack8(sc));
             const u32x4 yy = yv[i][j];
             const float b[8] = {bf16lo(yy.x), bf16hi(yy.x), bf16lo(yy.y), bf16hi(yy.y), bf16lo(yy.z), bf16hi(yy.z), bf16lo(yy.w), bf16hi(yy.w)};
 #pragma unroll
