@@ -46,16 +46,17 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 //   perm_rank : rank of every slot among the same-expert slots of its block
 //   sched     : tile schedule of the grouped GEMMs (header + two int arrays)
 //   zero_page : 256 zero bytes, the source of k-rows past the end of a ragged contraction
-//   h, dg, du : bf16 [N,f] intermediates of the expert FFN (H in forward; H, dG, dU in backward)
+//   h, dg, du : bf16 [N,f] intermediates of the expert FFN (H in forward; H, dG, dU in backward): with x_perm these are
+//               the 3 d_ffn + d_model values per row of the activation-memory model of Section III-A
 struct WsLayout {
   size_t perm_hist, perm_hist_bytes;
   size_t perm_rank, perm_rank_bytes;
   size_t sched, sched_bytes;
   size_t zero_page;
   size_t splitk_counters;   // kSplitCounters int32: arrivals per split tile
-  size_t splitk_partial;    // kSplitParts fp32 tiles of 256 x 256: partial sums of the tiles whose K range is split
+  size_t splitk_partial;    // kSplitParts fp32 tiles of up to 320 x 256: partial sums of the tiles whose K range is split
   size_t h, dg, du, nf_bytes;
-  size_t g_re, u_re;        // [N,f] bf16: G, U when the caller does not keep them (checkpointed forward, recomputing backward)
+  size_t g_re, u_re;        // G, U when the caller does not keep them (checkpointed forward, recomputing backward): = dg, du
   size_t router_offsets;    // 8 int32: {0, T} and {0, E}, the one-segment "offsets" of the router's GEMMs
   size_t dl_hi, dl_lo;      // [T, Epad] bf16: head and remainder of the fp32 dlogits (Epad = E rounded up to 64)
   size_t total;
@@ -81,13 +82,15 @@ inline WsLayout ws_layout(const Dims& D) {
   L.splitk_counters = off;
   off += round_up((size_t)kSplitCounters * sizeof(int32_t), 256);
   L.splitk_partial = off;
-  off += (size_t)kSplitParts * 256 * 256 * sizeof(float);
+  off += (size_t)kSplitParts * 320 * 256 * sizeof(float);
   L.nf_bytes = round_up((size_t)D.N * D.f * sizeof(uint16_t), 256);
   L.h = off; off += L.nf_bytes;
   L.dg = off; off += L.nf_bytes;
   L.du = off; off += L.nf_bytes;
-  L.g_re = off; off += L.nf_bytes;
-  L.u_re = off; off += L.nf_bytes;
+  // G, U that the caller does not keep share the memory of dG, dU: the kernel that consumes them (dH with the
+  // d(SwiGLU) epilogue) reads G, U and writes dG, dU at the same element from the same lane, i.e. in place
+  L.g_re = L.dg;
+  L.u_re = L.du;
   L.router_offsets = off; off += 256;
   const size_t dl_bytes = round_up((size_t)D.T * round_up((size_t)D.E, 64) * sizeof(uint16_t) + 256, 256);
   L.dl_hi = off; off += dl_bytes;

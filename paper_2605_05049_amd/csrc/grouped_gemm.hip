@@ -45,9 +45,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int BK = 64;                          // k step
 constexpr int TILE = 256;                       // p extent, and (virtual) q extent, of a block tile
 constexpr int NTHREADS = 512;
-constexpr int OPERAND_BYTES = TILE * BK * 2;    // 32 KB per operand per stage
-constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;  // P + Q
-                                                // two stages = 128 KB of the 160 KB of LDS
+constexpr int TALL = TILE + 64;                 // rows of a tall tile: an expert's last full row tile plus up to 64 rows
+constexpr int OPERAND_BYTES = TILE * BK * 2;    // 32 KB per 256-row operand per stage
+constexpr int Q_STAGE_OFFSET = TALL * BK * 2;   // the Q operand follows the (up to 320-row, 40 KB) P operand
+constexpr int STAGE_BYTES = Q_STAGE_OFFSET + OPERAND_BYTES;  // P + Q = 72 KB
+                                                // two stages = 144 KB of the 160 KB of LDS
 constexpr int kNumXcd = 8;
 constexpr int kCusPerXcd = 32;
 #ifndef MOE_EARLY_ISSUE_AT
@@ -197,6 +199,14 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int r0, int kk, in
   }
 }
 
+// Row tiles of an expert with n rows.  Without tall tiles: ceil(n / 256).  With them, a remainder of at most 64 rows
+// does not get a tile of its own (which would stream the expert's whole weight panel once more for a handful of rows)
+// but rides on the last full tile, which then has up to 320 rows: max(1, ceil((n - 64) / 256)).
+__host__ __device__ __forceinline__ int row_tiles_of(int n, int tall) {
+  if (n <= 0) return 0;
+  return tall ? max(1, (n - 64 + TILE - 1) / TILE) : (n + TILE - 1) / TILE;
+}
+
 // KIND 0: row-tile problem (p = ragged rows of an expert, k = k_dim);  KIND 1: wgrad (k = ragged rows).
 // NQ = 2: the q tile is two 128-wide halves from q0 and q1 (acc[0] = q0 result, acc[1] = q1 result at the same q).
 template <int KIND, bool P_RC, bool Q_RC, int NQ, int NPASS, int EPI>
@@ -224,13 +234,20 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   int split = 1, part = 0, part_slot = 0;
   int p_tile_idx;  // index of the tile along p
   if (KIND == 0) {
+    // Groups of 32 consecutive tiles of the logical order (about 4 row tiles x 8 column tiles of one expert: the tiles
+    // that share panels) are dealt round-robin to the XCDs, so that every XCD gets the same mix of experts and of tile
+    // heights (contiguous runs had handed a whole expert, with its tall or short tiles, to one XCD).  What is left after
+    // the last complete deal of 8 groups (fewer than 256 tiles) is cut into 8 equal runs, one per XCD.
     const int n_row_tiles = A.sched[0];
     const long long total = (long long)n_row_tiles * A.n_q_tiles;
-    const long long chunk = (total + kNumXcd - 1) / kNumXcd;
     const long long within = blockIdx.x / kNumXcd;
     const int xcd = blockIdx.x % kNumXcd;
-    const long long lo = (long long)xcd * chunk;
-    const long long cnt = max(min(chunk, total - lo), 0LL);  // tiles of this XCD
+    const long long deals = total / (kCusPerXcd * kNumXcd);          // rounds of 32 tiles every XCD gets
+    const long long dealt = deals * kCusPerXcd;                       // ... = tiles per XCD from the deals
+    const long long rest = total - dealt * kNumXcd;                   // < 256 tiles left over
+    const long long chunk = (rest + kNumXcd - 1) / kNumXcd;           // <= 32 per XCD
+    const long long lo = dealt * kNumXcd + (long long)xcd * chunk;
+    const long long cnt = max(min(chunk, total - lo), 0LL);           // left-over tiles of this XCD
     long long full = cnt;
     if (SPLITK) {
       const int rem = (int)(cnt % kCusPerXcd);
@@ -241,11 +258,14 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
       }
     }
     long long lid;
-    if (within < full) {
-      lid = lo + within;
+    if (within < dealt) {
+      lid = ((within / kCusPerXcd) * kNumXcd + xcd) * kCusPerXcd + within % kCusPerXcd;
+      split = 1;
+    } else if (within - dealt < full) {
+      lid = lo + (within - dealt);
       split = 1;
     } else {
-      const long long u = within - full;
+      const long long u = within - dealt - full;
       if (u >= (cnt - full) * split) return;
       lid = lo + full + u / split;
       part = (int)(u % split);
@@ -254,13 +274,13 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     const int u = (int)(lid / A.n_q_tiles);  // some row tile of the expert this block works for
     expert = A.sched[64 + u];
     const int e_lo = A.offsets[expert], e_hi = A.offsets[expert + 1];
-    const int e_tiles = (e_hi - e_lo + TILE - 1) / TILE;
+    const int e_tiles = row_tiles_of(e_hi - e_lo, A.sched[1]);
     const int first = A.sched[64 + A.max_tiles + u];  // index of the expert's first row tile
     const long long local = lid - (long long)first * A.n_q_tiles;
     const int qt = (int)(local / e_tiles);
     const int mt = (int)(local % e_tiles);
     p_row0 = e_lo + mt * TILE;
-    p_valid = min(TILE, e_hi - p_row0);
+    p_valid = (mt == e_tiles - 1) ? e_hi - p_row0 : TILE;   // (the last tile may be a tall one: up to 320 rows)
     p_tile_idx = mt;
     q0_col = qt * TQ;
     k_len = A.k_dim;
@@ -342,7 +362,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     const bool second = (NPASS == 2) && j >= nk_pass;
     const int k0 = (second ? j - nk_pass : j) * BK;
     issue_tile<P_RC, false, decltype(narrow_p)::value>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage, wave, lane);
-    issue_tile<Q_RC, NQ == 2, NARROW>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + OPERAND_BYTES, iwq, lane);
+    issue_tile<Q_RC, NQ == 2, NARROW>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + Q_STAGE_OFFSET, iwq, lane);
   };
   // the k-steps this block multiplies: all of them, or its part of a split tile
   const int kt_per = (nk + split - 1) / split;
@@ -354,7 +374,20 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   auto run = [&](auto pb_c) __attribute__((always_inline)) {
   constexpr int PB = decltype(pb_c)::value;
   // (a short tile leaves out the loads of the rows it does not have)
-  auto issue = [&](int j, char* stage) __attribute__((always_inline)) { issue_as(std::integral_constant<bool, NARROW || PB < 4>{}, j, stage); };
+  // a tall tile's rows 256.. are one more instruction per wavefront (instruction 32 + wave: rows 256 + 8 wave .. +7)
+  const unsigned pvo_tall = (PB == 5) ? load_offset<P_RC, false>(P, 32 + wave, lane) : 0u;
+  auto issue_tall = [&](int j, char* stage) __attribute__((always_inline)) {
+    if (PB == 5 && (32 + wave) * 8 < p_valid) {
+      const bool second = (NPASS == 2) && j >= nk_pass;
+      const int k0 = (second ? j - nk_pass : j) * BK;
+      direct_load16(P.base0 + (second ? p_pass_delta : (ptrdiff_t)0) + k0, pvo_tall, stage + (32 + wave) * 1024);
+    }
+  };
+  auto issue = [&](int j, char* stage) __attribute__((always_inline)) {
+    issue_as(std::integral_constant<bool, NARROW || PB < 4>{}, j, stage);
+    issue_tall(j, stage);
+  };
+  if (kt_begin < kt_end) issue_tall(kt_begin, stage0);   // (the rest of the first stage was requested above)
   const int wp = (wave & 1) * (PB * 32);  // p origin of this wavefront
   f32x16 acc[2][PB];  // [q sub-tile a][p sub-tile b]
 #pragma unroll
@@ -372,7 +405,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     __syncthreads();                     // ... and everyone's; everyone is also done reading the other stage
     if (late && kt + 1 < kt_end) issue(kt + 1, nxt);
     const char* p_lds = cur;
-    const char* q_lds = cur + OPERAND_BYTES;
+    const char* q_lds = cur + Q_STAGE_OFFSET;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       if (kk == MOE_EARLY_ISSUE_AT) {
@@ -411,7 +444,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   const bool f32_vector_ok = (A.c_ld & 3) == 0;  // 16-byte fp32 stores need rows that start on 16-byte boundaries
   if (SPLITK && split > 1) {
     // ---- a part of a split tile: fp32 partial tile -> workspace, then whoever arrives last reduces
-    float* mine = A.partial + (size_t)part_slot * (TILE * TILE);
+    float* mine = A.partial + (size_t)part_slot * (TALL * TILE);
 #pragma unroll
     for (int b = 0; b < PB; b++) {
 #pragma unroll
@@ -450,7 +483,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     __syncthreads();
     if ((arrived_before & 0xFFFF) != split - 1) return;
     if (!on_home_xcd || (arrived_before >> 16)) __threadfence();  // some part wrote through another XCD's L2
-    const float* parts = A.partial + (size_t)(part_slot - part) * (TILE * TILE);
+    const float* parts = A.partial + (size_t)(part_slot - part) * (TALL * TILE);
     // the valid part of the tile only: p_valid rows of ceil(q_valid / 8) groups of 8 columns, spread over all threads
     const int nqv = (q_valid + 7) >> 3;
     const int n_items = p_valid * nqv;
@@ -458,8 +491,8 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
       const int p = idx / nqv, q = (idx - p * nqv) * 8;
       float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       for (int sp = 0; sp < split; sp++) {
-        const f32x4 x0 = load_agent_f4(parts + (size_t)sp * (TILE * TILE) + p * TILE + q);
-        const f32x4 x1 = load_agent_f4(parts + (size_t)sp * (TILE * TILE) + p * TILE + q + 4);
+        const f32x4 x0 = load_agent_f4(parts + (size_t)sp * (TALL * TILE) + p * TILE + q);
+        const f32x4 x1 = load_agent_f4(parts + (size_t)sp * (TALL * TILE) + p * TILE + q + 4);
         x[0] += x0.x; x[1] += x0.y; x[2] += x0.z; x[3] += x0.w; x[4] += x1.x; x[5] += x1.y; x[6] += x1.z; x[7] += x1.w;
       }
       if (EPI == EPI_F32) {
@@ -571,23 +604,27 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     __builtin_amdgcn_wave_barrier();
   }
   };
-  if (KIND == 1 || p_valid > 128) run(std::integral_constant<int, 4>{});
+  constexpr bool CAN_BE_TALL = (KIND == 0 && !P_RC);   // (tall tiles add rows to a K-contiguous P stage)
+  if (CAN_BE_TALL && p_valid > TILE) run(std::integral_constant<int, CAN_BE_TALL ? 5 : 4>{});
+  else if (KIND == 1 || p_valid > 128) run(std::integral_constant<int, 4>{});
   else if (p_valid > 64) run(std::integral_constant<int, 2>{});
   else run(std::integral_constant<int, 1>{});
 }
 
-// Row-tile schedule: one thread per expert.  sched[0] = number of 256-row tiles; sched[64 + u] = expert of tile u;
+// Row-tile schedule: one thread per expert.  sched[0] = number of row tiles; sched[1] = whether an expert's last tile
+// may be a tall one; sched[64 + u] = expert of tile u;
 // sched[64 + max_tiles + u] = index of that expert's first tile; sched[64 + 2 max_tiles + i] = expert with the i-th most rows.
 // Also clears the zero page and the split-tile counters.
 __global__ __launch_bounds__(1024) void build_schedule_kernel(const int32_t* __restrict__ offsets, int32_t* __restrict__ sched,
                                                               uint32_t* __restrict__ zero_page, int32_t* __restrict__ counters,
-                                                              int Et, int max_tiles) {
+                                                              int Et, int max_tiles, int tall) {
   __shared__ int32_t scan[kMaxExperts];
   const int e = threadIdx.x;
   if (e < 64) zero_page[e] = 0u;
   if (e < kSplitCounters) counters[e] = 0;
   const int n = (e < Et) ? offsets[e + 1] - offsets[e] : 0;
-  const int nt = (n + TILE - 1) / TILE;
+  const int nt = row_tiles_of(n, tall);
+  if (e == 0) sched[1] = tall;
   scan[e] = nt;
   __syncthreads();
   for (int o = 1; o < kMaxExperts; o <<= 1) {
@@ -693,7 +730,7 @@ extern "C" int moe_grouped_ffn_fwd(const moe_shape* shape, const uint16_t* x_per
   uint16_t* h = reinterpret_cast<uint16_t*>(wsb + L.h);
   const int max_tiles = (int)sched_max_tiles(D);
   const long long ub_tiles = D.N / TILE + D.Et;  // sum_e ceil(n_e/256) <= N/256 + E'
-  MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles);
+  MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles, 1);
 
   GemmArgs A = {};
   A.sched = sched; A.max_tiles = max_tiles; A.offsets = offsets; A.Et = D.Et;
@@ -746,7 +783,7 @@ extern "C" int moe_grouped_ffn_bwd(const moe_shape* shape, const uint16_t* dy_pe
   A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
   A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
   // (also with no rows at all: the weight gradients read the expert order from the schedule)
-  MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles);
+  MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles, 1);
   if (D.N > 0) {
     // dH = dY Wd^T, then dG, dU and H from the saved G, U
     A.n_q_tiles = (D.f + TILE - 1) / TILE; A.q_dim = D.f; A.k_dim = D.d;
@@ -806,7 +843,7 @@ extern "C" int moe_router_bwd(const moe_shape* shape, const uint16_t* x, const u
   A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
   // dx_router[T,d] = dlogits W_r: rows = tokens, columns = d, K = E in two passes (head, remainder of dlogits);
   // P K-contiguous in the padded copies, Q = W_r read with k = expert row (R-contiguous, rows past E are zeros)
-  MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs, sched, zero_page, counters, 1, max_tiles);
+  MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs, sched, zero_page, counters, 1, max_tiles, 0);
   A.offsets = offs;
   A.n_q_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.d; A.k_dim = D.E;
   A.p0 = dl_hi; A.p1 = dl_lo; A.p_ld = Epad;
@@ -815,7 +852,7 @@ extern "C" int moe_router_bwd(const moe_shape* shape, const uint16_t* x, const u
   const long long row_tiles = (D.T + TILE - 1) / TILE;
   MOE_TRY((launch_gemm<0, false, true, 1, 2, EPI_BF16>("router_bwd_dx", A, row_tiles * A.n_q_tiles, st)));
   // dw_router[E,d] = dlogits^T X: rows = experts, columns = d, K = T in two passes; both operands R-contiguous
-  MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs + 4, sched, zero_page, counters, 1, max_tiles);
+  MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs + 4, sched, zero_page, counters, 1, max_tiles, 0);
   A.offsets = offs + 4; A.accumulate = accumulate ? 1 : 0;
   A.n_q_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.d; A.k_dim = (int)D.T;
   A.p0 = dl_hi; A.p1 = dl_lo; A.p_ld = Epad;
@@ -853,7 +890,7 @@ extern "C" int moe_grouped_ffn_bwd_recompute(const moe_shape* shape, const uint1
     int32_t* counters = reinterpret_cast<int32_t*>(wsb + L.splitk_counters);
     const int max_tiles = (int)sched_max_tiles(D);
     const long long ub_tiles = D.N / TILE + D.Et;
-    MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles);
+    MOE_LAUNCH("ffn_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offsets, sched, zero_page, counters, D.Et, max_tiles, 1);
     GemmArgs A = {};
     A.sched = sched; A.max_tiles = max_tiles; A.offsets = offsets; A.Et = D.Et;
     A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);

@@ -37,8 +37,8 @@ def test_status_strings(lib):
 def test_workspace_bytes_follows_the_shape(lib):
     s = moe.Shape(256, 512, 1024, 8, 2)
     n = moe.workspace_bytes(s)
-    # three [N,f] bf16 intermediates dominate (H, dG, dU)
-    assert n >= 3 * s.N * s.d_ffn * 2 and n % 256 == 0
+    # three [N,f] bf16 intermediates (H, dG, dU) plus the fixed 80 MiB of partial tiles of split contractions
+    assert 3 * s.N * s.d_ffn * 2 + (80 << 20) <= n <= 3 * s.N * s.d_ffn * 2 + (82 << 20) and n % 256 == 0
     assert moe.workspace_bytes(moe.Shape(512, 512, 1024, 8, 2)) > n
     assert moe.workspace_bytes(moe.Shape(256, 500, 1024, 8, 2)) == 0       # d not a multiple of 64
     assert moe.workspace_bytes(moe.Shape(256, 512, 1024, 8, 9)) == 0       # k > E

@@ -351,6 +351,50 @@ def test_grouped_ffn_fwd_bwd(moe, T, d, f, E, k, Es, dead):
         assert torch.all(gwu[e] == base)
 
 
+@pytest.mark.parametrize("d,f", [(128, 256), (256, 1088)])
+def test_grouped_ffn_every_tile_height(moe, d, f):
+    """Experts whose row counts hit every height class of a row tile and both sides of every class boundary: 1..64 rows
+    (one 32-row block per wavefront), 65..128, 129..256, 257..320 (a full tile that carries up to 64 more rows), 321
+    (a full tile plus a short one), an empty expert, and a multi-tile expert whose remainder rides on its last tile.
+    (f = 1088 = 4 * 256 + 64 also puts a 64-wide last column tile and a K long enough for the split tail on every class.)"""
+    counts = np.array([1, 31, 33, 64, 65, 128, 129, 256, 257, 300, 320, 321, 0, 577, 512 + 65], dtype=np.int64)
+    E, N = counts.size, int(counts.sum())
+    offsets = np.zeros(E + 1, dtype=np.int32)
+    offsets[1:] = np.cumsum(counts)
+    shape = W.MoEShape(N, d, f, E, 1)        # (T = N rows with one slot each: only the sizes matter here)
+    s = moe.Shape.of(shape)
+    rng = np.random.default_rng(d + f)
+    xp_bits = W.f32_to_bf16_bits(rng.standard_normal((N, d)).astype(np.float32))
+    dy_bits = W.f32_to_bf16_bits((rng.standard_normal((N, d)) * rng.random((N, 1))).astype(np.float32))
+    wgb, wub, wdb = W.make_expert_weights(shape, seed=1, std=0.05)
+    ws = ws_for(moe, s)
+    d_xp, d_off = dev_bf16(xp_bits), dev(offsets)
+    d_wg, d_wu, d_wd = dev_bf16(wgb), dev_bf16(wub), dev_bf16(wdb)
+    y = torch.full((N, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    sg = torch.full((N, f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    su = torch.full((N, f), float("nan"), dtype=torch.bfloat16, device="cuda")
+    moe.moe_grouped_ffn_fwd(s, d_xp, d_off, d_wg, d_wu, d_wd, y, sg, su, ws)
+    xp, dyp = W.bf16_bits_to_f32(xp_bits), W.bf16_bits_to_f32(dy_bits)
+    wg, wu, wd = W.bf16_bits_to_f32(wgb), W.bf16_bits_to_f32(wub), W.bf16_bits_to_f32(wdb)
+    Y, G, U = O.grouped_ffn_fwd(xp, offsets, wg, wu, wd)
+    qY, qG, qU = O.grouped_ffn_fwd_scales(xp, offsets, wg, wu, wd)
+    assert_close(host_f32(sg), G, qG, what="save_g")
+    assert_close(host_f32(su), U, qU, what="save_u")
+    assert_close(host_f32(y), Y, qY, what="y_perm")
+    dxp = torch.full((N, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    gwg = torch.full((E, d, f), 7.0, dtype=torch.float32, device="cuda")
+    gwu = torch.full((E, d, f), 7.0, dtype=torch.float32, device="cuda")
+    gwd = torch.full((E, f, d), 7.0, dtype=torch.float32, device="cuda")
+    moe.moe_grouped_ffn_bwd(s, dev_bf16(dy_bits), d_xp, d_off, d_wg, d_wu, d_wd, sg, su, dxp, gwg, gwu, gwd, 0, ws)
+    dX, dWg, dWu, dWd = O.grouped_ffn_bwd(dyp, xp, offsets, wg, wu, wd)
+    qX, qWg, qWu, qWd = O.grouped_ffn_bwd_scales(dyp, xp, offsets, wg, wu, wd)
+    assert_close(host_f32(dxp), dX, qX, what="dx_perm")
+    assert_close(gwg.cpu().numpy(), dWg, qWg, what="dw_gate")
+    assert_close(gwu.cpu().numpy(), dWu, qWu, what="dw_up")
+    assert_close(gwd.cpu().numpy(), dWd, qWd, what="dw_down")
+    assert not gwg[12].any() and not gwd[12].any()          # the empty expert
+
+
 # ---------------------------------------------------------------------------------------------------------
 # the whole layer, forward + backward, against the per-token definition
 # ---------------------------------------------------------------------------------------------------------
