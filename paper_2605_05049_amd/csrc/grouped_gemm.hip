@@ -29,8 +29,9 @@
 // row bits), and the fragment reads apply the same swizzle.  Every request is a whole 128-byte line (KC) or four of
 // them (RC): the vector L1 handles about one line per two cycles whatever part of it is used.  Rows past the end of
 // a ragged K (weight gradients) are fetched from a zeroed page.  Row tiles of the ragged dimension come from a
-// device-built schedule (no host sync on the counts); the block-id -> tile map hands each XCD a contiguous run of
-// tiles so that tiles sharing a weight panel meet in one L2.
+// device-built schedule (no host sync on the counts); the block-id -> tile map deals groups of 32 consecutive tiles
+// (super-tiles of 8 x 4 tiles for the weight gradients) round-robin to the XCDs, so that tiles sharing a panel meet in
+// one L2 and every XCD gets the same mix of experts.
 #include "common.h"
 
 #include <type_traits>
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   const int wq = wave >> 1;         // 0..3 along q
   const int late = wave >> 2;       // wavefronts 4..7 share their SIMDs with 0..3 and load at another time of the step
 
-  // ---- block id -> tile (each XCD takes a contiguous run of the logical tile order) ----
+  // ---- block id -> tile ----
   int expert, p_row0 = 0, p_valid, q0_col, k_len;
   size_t krow0 = 0;
   // Tail split (row-tile problems with a plain bf16 or fp32 output): when an XCD's last round of tiles would occupy at most half of its
