@@ -57,8 +57,9 @@ struct WsLayout {
   size_t splitk_partial;    // kSplitParts fp32 tiles of up to 320 x 256: partial sums of the tiles whose K range is split
   size_t h, dg, du, nf_bytes;
   size_t g_re, u_re;        // G, U when the caller does not keep them (checkpointed forward, recomputing backward): = dg, du
-  size_t router_offsets;    // 8 int32: {0, T} and {0, E}, the one-segment "offsets" of the router's GEMMs
+  size_t router_offsets;    // 64 int32: {0, T}, {0, E} (one-segment "offsets" of the router's GEMMs) and the bounds of the parts of T
   size_t dl_hi, dl_lo;      // [T, Epad] bf16: head and remainder of the fp32 dlogits (Epad = E rounded up to 64)
+  size_t w_router_t;        // [d, 128] bf16 at most: W_r transposed and zero-padded (router backward, E <= 128)
   size_t total;
 };
 
@@ -95,6 +96,7 @@ inline WsLayout ws_layout(const Dims& D) {
   const size_t dl_bytes = round_up((size_t)D.T * round_up((size_t)D.E, 64) * sizeof(uint16_t) + 256, 256);
   L.dl_hi = off; off += dl_bytes;
   L.dl_lo = off; off += dl_bytes;
+  L.w_router_t = off; off += round_up((size_t)D.d * 128 * sizeof(uint16_t), 256);
   L.total = off;
   return L;
 }
@@ -103,6 +105,15 @@ inline WsLayout ws_layout(const Dims& D) {
 #define MOE_REQUIRE_ALIGNED(p) do { if (!::moe::aligned((p), 16)) return MOE_ERR_ALIGN; } while (0)
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_RUNTIME; }
+
+// Router backward pieces that live beside the router's forward kernel (router.hip) and are launched from the entry
+// point that also launches the grouped GEMM kernel (grouped_gemm.hip).
+void launch_router_prepare(hipStream_t st, const float* dlogits, const uint16_t* w_router, uint16_t* hi, uint16_t* lo, uint16_t* w_t,
+                           int32_t* offsets2, int32_t* part_order, uint32_t* zero_page, int T, int E, int Epad, int Ek, int d, int S,
+                           int part_rows);
+void launch_router_bwd_dx(hipStream_t st, const uint16_t* dl_hi, const uint16_t* dl_lo, const uint16_t* w_t, uint16_t* dx, int T, int d,
+                          int E, int Epad);
+void launch_router_dw_reduce(hipStream_t st, const float* partial, float* dw, int S, int E, int d, int ldp, int accumulate);
 
 // Optional per-launch timing (moe_profile_* in the ABI).  While enabled, every kernel launch of the library is
 // bracketed by two HIP events on the launch stream; disabled (the default) it costs one branch.
@@ -124,18 +135,18 @@ struct ProfScope {
 // device helpers
 // ---------------------------------------------------------------------------------------------------------
 
-// bf16 <-> fp32 on raw bit patterns.  Round-to-nearest-even; NaN stays NaN.
+// bf16 <-> fp32 on raw bit patterns.  fp32 -> bf16 is the hardware conversion (v_cvt_pk_bf16_f32: two values per
+// instruction, round-to-nearest-even, NaN stays NaN).
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16(float v) {
-  uint32_t u = __float_as_uint(v);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
 __device__ __forceinline__ float bf16lo(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  typedef __bf16 bf16_pair __attribute__((ext_vector_type(2)));
+  typedef float f32_pair __attribute__((ext_vector_type(2)));
+  const f32_pair v = {lo, hi};
+  const bf16_pair b = __builtin_convertvector(v, bf16_pair);
+  return __builtin_bit_cast(uint32_t, b);
 }
+__device__ __forceinline__ uint16_t f32_to_bf16(float v) { return (uint16_t)(pack_bf16(v, 0.f) & 0xffffu); }
 
 }  // namespace moe

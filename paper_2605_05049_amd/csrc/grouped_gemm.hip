@@ -34,6 +34,7 @@
 // one L2 and every XCD gets the same mix of experts.
 #include "common.h"
 
+#include <algorithm>
 #include <type_traits>
 
 namespace moe {
@@ -83,6 +84,7 @@ struct GemmArgs {
   uint16_t* c0; uint16_t* c1; uint16_t* c2; size_t c_ld;   // bf16 outputs (row-major, ld = q_dim)
   const uint16_t* g_in; const uint16_t* u_in;              // saved G, U for the d(SwiGLU) epilogue
   float* f0; float* f1; size_t f_expert_stride;            // fp32 outputs of the wgrads
+  int sum_halves;          // NQ == 2 with fp32 output: write the sum of the two halves' results to f0 (f1 unused)
 };
 
 // One 256-wide operand of a tile, possibly made of two 128-wide halves from two tensors.
@@ -533,6 +535,11 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
 #pragma unroll
           for (int n = 0; n < NQ; n++) {
             float4 v = *reinterpret_cast<const float4*>(wlds + n * 8192 + r * PITCH + q * 4);
+            if (NQ == 2 && A.sum_halves) {   // (uniform over the launch)
+              if (n == 1) break;
+              const float4 v1 = *reinterpret_cast<const float4*>(wlds + 8192 + r * PITCH + q * 4);
+              v.x += v1.x; v.y += v1.y; v.z += v1.z; v.w += v1.w;
+            }
             float* dst = (n == 0 ? A.f0 : A.f1) + o;
             if (!NARROW || (f32_vector_ok && q_base + q + 4 <= q_valid)) {   // (d_model, d_ffn are multiples of 64)
               if (A.accumulate) {
@@ -651,26 +658,6 @@ __global__ __launch_bounds__(1024) void build_schedule_kernel(const int32_t* __r
       sched[64 + max_tiles + first + i] = first;
     }
   }
-}
-
-// Router helpers.  Writes the two one-segment offset arrays ({0, T} for problems whose rows are tokens, {0, E} for the
-// one whose rows are experts) and, when dlogits is given, splits it into a bf16 head and a bf16 remainder
-// (hi = bf16(v), lo = bf16(v - hi): hi + lo carries 16 significand bits of v), zero-padded to Epad columns.
-__global__ __launch_bounds__(256) void router_prepare_kernel(const float* __restrict__ dlogits, uint16_t* __restrict__ hi,
-                                                             uint16_t* __restrict__ lo, int32_t* __restrict__ offsets2,
-                                                             int T, int E, int Epad) {
-  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i == 0) {
-    offsets2[0] = 0; offsets2[1] = T;
-    offsets2[4] = 0; offsets2[5] = E;
-  }
-  if (dlogits == nullptr || i >= (long long)T * Epad) return;
-  const int t = (int)(i / Epad), e = (int)(i % Epad);
-  const float v = e < E ? dlogits[(size_t)t * E + e] : 0.f;
-  const uint32_t h2 = pack_bf16(v, 0.f) & 0xFFFFu;
-  const float hf = bf16lo(h2);
-  hi[i] = (uint16_t)h2;
-  lo[i] = (uint16_t)(pack_bf16(v - hf, 0.f) & 0xFFFFu);
 }
 
 // Blocks of a weight-gradient launch: whole rounds of one 32-tile super-tile per XCD.
@@ -835,32 +822,55 @@ extern "C" int moe_router_bwd(const moe_shape* shape, const uint16_t* x, const u
   uint16_t* dl_lo = reinterpret_cast<uint16_t*>(wsb + L.dl_lo);
   const int max_tiles = (int)sched_max_tiles(D);
   const int Epad = (int)round_up((size_t)D.E, 64);
-  const long long n_split = (long long)D.T * Epad;
-  MOE_LAUNCH("router_prepare", st, router_prepare_kernel, dim3((unsigned)((n_split + 255) / 256)), dim3(256), 0, st, dlogits, dl_hi, dl_lo,
-             offs, (int)D.T, (int)D.E, Epad);
+  const bool skinny_dx = D.E <= 128;                          // (the dx kernel keeps W_r^T for 128 experts in registers)
+  const int Ek = D.E <= 32 ? 32 : (D.E <= 64 ? 64 : 128);    // experts padded to the dx kernel's k-groups
+  uint16_t* w_t = reinterpret_cast<uint16_t*>(wsb + L.w_router_t);
+  float* partial = reinterpret_cast<float*>(wsb + L.splitk_partial);
+  // dW_r: the token range is cut into S parts, each a "segment" of the weight-gradient kernel with its own fp32 output
+  // [d, ldp] in the partial-tile area; S gives every CU a tile if the area allows
+  const int n_p_tiles = (int)((D.d + TILE - 1) / TILE), n_q_tiles = (int)((D.E + 127) / 128);
+  const int ldp = (int)round_up((size_t)D.E, 4);
+  const size_t part_bytes = (size_t)D.d * ldp * sizeof(float);
+  const size_t area_bytes = (size_t)kSplitParts * 320 * 256 * sizeof(float);
+  long long S = (256 + (long long)n_p_tiles * n_q_tiles - 1) / ((long long)n_p_tiles * n_q_tiles);
+  S = std::min<long long>(S, 32);
+  S = std::min<long long>(S, (long long)(area_bytes / part_bytes));
+  S = std::min<long long>(S, (D.T + 63) / 64);
+  if (S < 1) return MOE_ERR_WORKSPACE;   // (d * E beyond 21 M elements: not a router)
+  const int part_rows = (int)round_up((size_t)((D.T + S - 1) / S), 64);
+  launch_router_prepare(st, dlogits, w_router, dl_hi, dl_lo, skinny_dx ? w_t : nullptr, offs, sched + 64 + 2 * max_tiles, zero_page, (int)D.T,
+                        (int)D.E, Epad, Ek, (int)D.d, (int)S, part_rows);
   GemmArgs A = {};
   A.sched = sched; A.max_tiles = max_tiles; A.Et = 1; A.accumulate = 0;
   A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
-  A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
-  // dx_router[T,d] = dlogits W_r: rows = tokens, columns = d, K = E in two passes (head, remainder of dlogits);
-  // P K-contiguous in the padded copies, Q = W_r read with k = expert row (R-contiguous, rows past E are zeros)
-  MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs, sched, zero_page, counters, 1, max_tiles, 0);
-  A.offsets = offs;
-  A.n_q_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.d; A.k_dim = D.E;
-  A.p0 = dl_hi; A.p1 = dl_lo; A.p_ld = Epad;
-  A.q0 = w_router; A.q1 = w_router; A.q_ld = D.d; A.q_expert_stride = 0;
-  A.c0 = dx_router; A.c_ld = D.d;
-  const long long row_tiles = (D.T + TILE - 1) / TILE;
-  MOE_TRY((launch_gemm<0, false, true, 1, 2, EPI_BF16>("router_bwd_dx", A, row_tiles * A.n_q_tiles, st)));
-  // dw_router[E,d] = dlogits^T X: rows = experts, columns = d, K = T in two passes; both operands R-contiguous
-  MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs + 4, sched, zero_page, counters, 1, max_tiles, 0);
-  A.offsets = offs + 4; A.accumulate = accumulate ? 1 : 0;
-  A.n_q_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.d; A.k_dim = (int)D.T;
-  A.p0 = dl_hi; A.p1 = dl_lo; A.p_ld = Epad;
-  A.q0 = x; A.q1 = x; A.q_ld = D.d; A.q_expert_stride = 0;
-  A.c0 = nullptr; A.f0 = dw_router; A.f_expert_stride = 0; A.c_ld = D.d;
-  const long long e_tiles = (D.E + TILE - 1) / TILE;
-  MOE_TRY((launch_gemm<0, true, true, 1, 2, EPI_F32>("router_bwd_dw", A, e_tiles * A.n_q_tiles, st)));
+  A.partial = partial; A.counters = counters;
+  if (skinny_dx) {
+    launch_router_bwd_dx(st, dl_hi, dl_lo, w_t, dx_router, (int)D.T, (int)D.d, (int)D.E, Epad);
+  } else {
+    // dx_router[T,d] = dlogits W_r on the grouped GEMM kernel: rows = tokens, columns = d, K = E in two passes (head,
+    // remainder of dlogits); P K-contiguous in the padded copies, Q = W_r read with k = expert row (R-contiguous)
+    MOE_LAUNCH("router_schedule", st, build_schedule_kernel, dim3(1), dim3(1024), 0, st, offs, sched, zero_page, counters, 1, max_tiles, 0);
+    A.offsets = offs;
+    A.n_q_tiles = (D.d + TILE - 1) / TILE; A.q_dim = D.d; A.k_dim = D.E;
+    A.p0 = dl_hi; A.p1 = dl_lo; A.p_ld = Epad;
+    A.q0 = w_router; A.q1 = w_router; A.q_ld = D.d; A.q_expert_stride = 0;
+    A.c0 = dx_router; A.c_ld = D.d;
+    const long long row_tiles = (D.T + TILE - 1) / TILE;
+    MOE_TRY((launch_gemm<0, false, true, 1, 2, EPI_BF16>("router_bwd_dx", A, row_tiles * A.n_q_tiles, st)));
+  }
+  // dW_r^T[c, e] per part = X_part^T dlogits_part: the weight-gradient kernel with p = columns of x, q = experts (the
+  // head and the remainder of dlogits as the two halves of the q tile, their results added in the epilogue), k = the
+  // part's tokens; then the parts are added in order and transposed into dW_r.  (The segment order and the zero page
+  // that this kernel reads of a schedule were written by the prepare kernel; a dx launch above leaves them as they are.)
+  GemmArgs B = {};
+  B.sched = sched; B.max_tiles = max_tiles; B.offsets = offs + 8; B.Et = (int)S; B.accumulate = 0;
+  B.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
+  B.p_dim = D.d; B.n_p_tiles = n_p_tiles; B.q_dim = D.E; B.n_q_tiles = n_q_tiles;
+  B.p0 = x; B.p_ld = D.d;
+  B.q0 = dl_hi; B.q1 = dl_lo; B.q_ld = Epad;
+  B.f0 = partial; B.f1 = nullptr; B.f_expert_stride = (size_t)D.d * ldp; B.c_ld = ldp; B.sum_halves = 1;
+  MOE_TRY((launch_gemm<1, true, true, 2, 1, EPI_F32>("router_bwd_dw", B, wgrad_blocks((int)S, n_p_tiles, n_q_tiles), st)));
+  launch_router_dw_reduce(st, partial, dw_router, (int)S, (int)D.E, (int)D.d, ldp, accumulate ? 1 : 0);
   return launch_status();
 }
 

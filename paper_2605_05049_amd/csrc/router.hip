@@ -14,6 +14,8 @@
 // pattern), D[expert][token]: lane l holds token l%16 and experts 4 (l/16) .. +3, i.e. 4 consecutive logits of a row.
 #include "common.h"
 
+#include <type_traits>
+
 namespace moe {
 
 typedef __bf16 r_bf16x8 __attribute__((ext_vector_type(8)));
@@ -36,13 +38,15 @@ __global__ __launch_bounds__(kRouterWaves * kWave) void router_fwd_kernel(const 
   const int per = (n_groups + kRouterWaves - 1) / kRouterWaves;
   const int g_begin = min(wave * per, n_groups), g_end = min(n_groups, g_begin + per);
 
-  // rows past the end are clamped onto the last valid one (never stored)
-  const uint16_t* xrow[TB];
+  // rows past the end are clamped onto the last valid one (never stored); a row is addressed by the block's base
+  // (wave-uniform) plus a 32-bit element offset per lane
+  const uint16_t* xbase = x + (size_t)t0 * d;
+  const uint16_t* wbase = w_router + (size_t)e0 * d;
+  unsigned xoff[TB], woff[NEB];
 #pragma unroll
-  for (int b = 0; b < TB; b++) xrow[b] = x + (size_t)min(t0 + 16 * b + n, T - 1) * d + 8 * kg;
-  const uint16_t* wrow[NEB];
+  for (int b = 0; b < TB; b++) xoff[b] = (unsigned)min(16 * b + n, T - 1 - t0) * (unsigned)d + 8 * kg;
 #pragma unroll
-  for (int m = 0; m < NEB; m++) wrow[m] = w_router + (size_t)min(e0 + 16 * m + n, E - 1) * d + 8 * kg;
+  for (int m = 0; m < NEB; m++) woff[m] = (unsigned)min(16 * m + n, E - 1 - e0) * (unsigned)d + 8 * kg;
 
   r_f32x4 acc[NEB][TB];
 #pragma unroll
@@ -50,29 +54,43 @@ __global__ __launch_bounds__(kRouterWaves * kWave) void router_fwd_kernel(const 
 #pragma unroll
     for (int b = 0; b < TB; b++) acc[m][b] = r_f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // fragments of k-group g: x from HBM (touched once: non-temporal), W_r from the L2
-  auto load = [&](r_bf16x8 (&xf)[TB], r_bf16x8 (&wf)[NEB], int g) __attribute__((always_inline)) {
+  // DEPTH k-groups in flight (as many as the registers of this TB x NEB allow): while one is multiplied the loads of
+  // the next DEPTH - 1 are already out.  x from HBM (touched once: non-temporal), W_r from the L2.
+  constexpr int DEPTH = (TB + NEB) <= 2 ? 8 : ((TB + NEB) <= 6 ? 4 : 2);
+  r_bf16x8 xf[DEPTH][TB], wf[DEPTH][NEB];
+  auto load = [&](auto slot_c, int g) __attribute__((always_inline)) {
+    constexpr int SL = decltype(slot_c)::value;
 #pragma unroll
-    for (int b = 0; b < TB; b++) xf[b] = __builtin_nontemporal_load(reinterpret_cast<const r_bf16x8*>(xrow[b] + (size_t)g * 32));
+    for (int b = 0; b < TB; b++) xf[SL][b] = __builtin_nontemporal_load(reinterpret_cast<const r_bf16x8*>(xbase + xoff[b] + (size_t)g * 32));
 #pragma unroll
-    for (int m = 0; m < NEB; m++) wf[m] = *reinterpret_cast<const r_bf16x8*>(wrow[m] + (size_t)g * 32);
+    for (int m = 0; m < NEB; m++) wf[SL][m] = *reinterpret_cast<const r_bf16x8*>(wbase + woff[m] + (size_t)g * 32);
   };
-  auto multiply = [&](const r_bf16x8 (&xf)[TB], const r_bf16x8 (&wf)[NEB]) __attribute__((always_inline)) {
+  auto multiply = [&](auto slot_c) __attribute__((always_inline)) {
+    constexpr int SL = decltype(slot_c)::value;
 #pragma unroll
     for (int m = 0; m < NEB; m++)
 #pragma unroll
-      for (int b = 0; b < TB; b++) acc[m][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[m], xf[b], acc[m][b], 0, 0, 0);
+      for (int b = 0; b < TB; b++) acc[m][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[SL][m], xf[SL][b], acc[m][b], 0, 0, 0);
   };
-  // two k-groups in flight: while one is multiplied the next one's loads are already out
-  r_bf16x8 x0[TB], x1[TB], w0[NEB], w1[NEB];
-  if (g_begin < g_end) load(x0, w0, g_begin);
-  for (int g = g_begin; g < g_end; g += 2) {
-    if (g + 1 < g_end) load(x1, w1, g + 1);
-    multiply(x0, w0);
-    if (g + 1 < g_end) {
-      if (g + 2 < g_end) load(x0, w0, g + 2);
-      multiply(x1, w1);
-    }
+  auto for_each_slot = [&](auto&& f) __attribute__((always_inline)) {
+    f(std::integral_constant<int, 0>{});
+    if constexpr (DEPTH > 1) f(std::integral_constant<int, 1>{});
+    if constexpr (DEPTH > 2) { f(std::integral_constant<int, 2>{}); f(std::integral_constant<int, 3>{}); }
+    if constexpr (DEPTH > 4) { f(std::integral_constant<int, 4>{}); f(std::integral_constant<int, 5>{}); f(std::integral_constant<int, 6>{}); f(std::integral_constant<int, 7>{}); }
+  };
+  // prologue: slots 0 .. DEPTH-2 take k-groups g_begin .. g_begin + DEPTH - 2
+  for_each_slot([&](auto sc) __attribute__((always_inline)) {
+    constexpr int SL = decltype(sc)::value;
+    if (SL < DEPTH - 1 && g_begin + SL < g_end) load(sc, g_begin + SL);
+  });
+  for (int g = g_begin; g < g_end; g += DEPTH) {
+    for_each_slot([&](auto sc) __attribute__((always_inline)) {
+      constexpr int SL = decltype(sc)::value;
+      if (g + SL < g_end) {
+        if (g + SL + DEPTH - 1 < g_end) load(std::integral_constant<int, (SL + DEPTH - 1) % DEPTH>{}, g + SL + DEPTH - 1);
+        multiply(sc);
+      }
+    });
   }
 
   // the 8 parts of K meet in LDS, one 16 x 16 block at a time, and are added in part order; thread i of the block
@@ -104,6 +122,212 @@ static void launch_router_fwd(hipStream_t st, dim3 grid, int neb, const uint16_t
   else if (neb <= 2) MOE_LAUNCH("router_fwd", st, (router_fwd_kernel<TB, 2>), grid, block, 0, st, x, w_router, logits, T, E, d);
   else if (neb <= 4) MOE_LAUNCH("router_fwd", st, (router_fwd_kernel<TB, 4>), grid, block, 0, st, x, w_router, logits, T, E, d);
   else MOE_LAUNCH("router_fwd", st, (router_fwd_kernel<TB, 8>), grid, block, 0, st, x, w_router, logits, T, E, d);
+}
+
+
+// ---------------------------------------------------------------------------------------------------------
+// Backward of the linear map: helpers for dx_router = dlogits W_r and dW_r = dlogits^T x.
+// ---------------------------------------------------------------------------------------------------------
+
+// Splits dlogits into a bf16 head and a bf16 remainder (hi = bf16(v), lo = bf16(v - hi): hi + lo carries 16
+// significand bits of v), zero-padded to Epad columns; writes W_r^T [d, Ek] bf16 (Ek = E rounded up to 32, zero
+// padded), so that the expert index is the contiguous one for the dx kernel's fragments; writes the offset arrays of
+// the GEMM-path problems: {0, T} at [0..1], {0, E} at [4..5], and at [8 .. 8 + S] the S + 1 bounds of the S equal
+// parts of the token range that the dW_r contraction is cut into; and what the weight-gradient kernel reads of a
+// schedule: the order of its segments (the parts in turn: they are equally long but for the last) and the zero page.
+__global__ __launch_bounds__(256) void router_prepare_kernel(const float* __restrict__ dlogits, const uint16_t* __restrict__ w_router,
+                                                             uint16_t* __restrict__ hi, uint16_t* __restrict__ lo,
+                                                             uint16_t* __restrict__ w_t, int32_t* __restrict__ offsets2,
+                                                             int32_t* __restrict__ part_order, uint32_t* __restrict__ zero_page,
+                                                             int T, int E, int Epad, int Ek, int d, int S, int part_rows) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i == 0) {
+    offsets2[0] = 0; offsets2[1] = T;
+    offsets2[4] = 0; offsets2[5] = E;
+  }
+  if (i <= S) offsets2[8 + i] = (int)min((long long)T, i * part_rows);
+  if (i < S) part_order[i] = (int)i;
+  if (i < 64) zero_page[i] = 0u;
+  if (w_t != nullptr && i < (long long)d * (Ek / 8)) {
+    const int dcol = (int)(i % d), ec = (int)(i / d);
+    uint32_t v[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const int e0 = 8 * ec + 2 * j;
+      const uint32_t a = e0 < E ? w_router[(size_t)e0 * d + dcol] : 0u;
+      const uint32_t b = e0 + 1 < E ? w_router[(size_t)(e0 + 1) * d + dcol] : 0u;
+      v[j] = a | (b << 16);
+    }
+    *reinterpret_cast<uint4*>(w_t + (size_t)dcol * Ek + 8 * ec) = make_uint4(v[0], v[1], v[2], v[3]);
+  }
+  if (i >= (long long)T * Epad) return;
+  const int t = (int)(i / Epad), e = (int)(i % Epad);
+  const float v = e < E ? dlogits[(size_t)t * E + e] : 0.f;
+  const uint32_t h2 = pack_bf16(v, 0.f) & 0xFFFFu;
+  const float hf = bf16lo(h2);
+  hi[i] = (uint16_t)h2;
+  lo[i] = (uint16_t)(pack_bf16(v - hf, 0.f) & 0xFFFFu);
+}
+
+// dx_router[t, c] = sum_e dlogits[t, e] W_r[e, c] for E <= 128: T x d x E with E small, so its time is the time to
+// write dx once.  A block of 8 wavefronts owns `tokens_per_block` tokens and 1024 columns (2 KB of a token's row: narrower
+// blocks measured slower); a wavefront keeps the W_r^T fragments of its 128 columns (8 blocks of 16 columns x KG groups
+// of 32 experts) in registers for the whole block.
+// Per 16 tokens the block stages the head and the remainder of dlogits in LDS once (one 16-byte load per thread,
+// double-buffered, chunk positions XOR-swizzled with the token so that the fragment reads are conflict-free), every
+// wavefront multiplies (MFMA 16x16x32, columns as rows of the result so that a lane ends up with 4 consecutive
+// columns of a token), and bounces its 16 x 128 bf16 results through LDS to store 256 contiguous bytes per token.
+constexpr int kDxWaves = 8;
+constexpr int kDxColsPerWave = 128;
+constexpr int kDxBouncePitch = kDxColsPerWave * 2 + 16;   // bytes per staged token row (the +16 spreads the banks)
+
+template <int KG>
+__global__ __launch_bounds__(kDxWaves * kWave) void router_bwd_dx_kernel(const uint16_t* __restrict__ dl_hi, const uint16_t* __restrict__ dl_lo,
+                                                                         const uint16_t* __restrict__ w_t, uint16_t* __restrict__ dx,
+                                                                         int T, int d, int Epad, int tokens_per_block) {
+  constexpr int Ek = 32 * KG;                  // experts padded to whole k-groups
+  constexpr int CH = 4 * KG;                   // 16-byte chunks per staged row
+  constexpr int ROWB = Ek * 2;                 // bytes per staged row
+  __shared__ __attribute__((aligned(16))) char dl_tile[2][2 * 16 * ROWB];       // [buffer][hi | lo][token][expert]
+  __shared__ __attribute__((aligned(16))) char bounce[kDxWaves][16 * kDxBouncePitch];
+  const int lane = threadIdx.x % kWave;
+  const int wave = threadIdx.x / kWave;
+  const int n = lane & 15, kg = lane >> 4;
+  const int t_begin = blockIdx.x * tokens_per_block;
+  const int t_end = min(T, t_begin + tokens_per_block);
+  const int c0 = blockIdx.y * (kDxWaves * kDxColsPerWave) + wave * kDxColsPerWave;   // first column of this wavefront
+  constexpr int MB = kDxColsPerWave / 16;                                              // blocks of 16 columns per wavefront
+  const int n_cb = max(0, min(MB, (d - c0) / 16));                                     // ... that exist
+
+  // W_r^T fragments: rows = columns of dx (clamped onto the last valid one where the wavefront has fewer)
+  r_bf16x8 wf[MB][KG];
+#pragma unroll
+  for (int m = 0; m < MB; m++) {
+    const int c = min(c0 + 16 * m + n, d - 1);
+#pragma unroll
+    for (int g = 0; g < KG; g++) wf[m][g] = *reinterpret_cast<const r_bf16x8*>(w_t + (size_t)c * Ek + 32 * g + 8 * kg);
+  }
+
+  // staging role of this thread: tensor (hi | lo), token row and chunk of the 16-token tile (threads past the tile idle)
+  const int s_part = threadIdx.x / (16 * CH);
+  const int s_row = (threadIdx.x / CH) % 16, s_ch = threadIdx.x % CH;
+  const bool stager = threadIdx.x < 2 * 16 * CH;
+  const uint16_t* s_src = (s_part == 0 ? dl_hi : dl_lo) + 8 * s_ch;
+  const int s_dst = (s_part * 16 + s_row) * ROWB + ((s_ch ^ ((s_row * KG) >> 2)) & (CH - 1)) * 16;
+  auto fetch = [&](int t0) -> uint4 {
+    const int t = min(t0 + s_row, T - 1);   // rows past the end are clamped (never stored)
+    return stager ? *reinterpret_cast<const uint4*>(s_src + (size_t)t * Epad) : make_uint4(0u, 0u, 0u, 0u);
+  };
+  // the next four tiles' pieces are in flight in registers (a tile's multiply is much shorter than a load's latency)
+  uint4 staged[4];
+#pragma unroll
+  for (int j = 0; j < 4; j++) staged[j] = (t_begin + 16 * j < t_end) ? fetch(t_begin + 16 * j) : make_uint4(0u, 0u, 0u, 0u);
+  int buf = 0;
+  for (int t4 = t_begin; t4 < t_end; t4 += 64) {
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    const int t0 = t4 + 16 * j;
+    if (t0 >= t_end) break;   // (uniform over the block)
+    if (stager) *reinterpret_cast<uint4*>(&dl_tile[buf][s_dst]) = staged[j];
+    __syncthreads();
+    if (t0 + 64 < t_end) staged[j] = fetch(t0 + 64);
+    r_f32x4 acc[MB];
+#pragma unroll
+    for (int m = 0; m < MB; m++) acc[m] = r_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int part = 1; part >= 0; part--) {   // remainder first, then the head
+#pragma unroll
+      for (int g = 0; g < KG; g++) {
+        const int ch = ((4 * g + kg) ^ ((n * KG) >> 2)) & (CH - 1);
+        const r_bf16x8 df = *reinterpret_cast<const r_bf16x8*>(&dl_tile[buf][(part * 16 + n) * ROWB + ch * 16]);
+#pragma unroll
+        for (int m = 0; m < MB; m++) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[m][g], df, acc[m], 0, 0, 0);
+      }
+    }
+    // acc[m][i] = dx[t0 + n][c0 + 16 m + 4 kg + i]: to LDS as bf16, back as 16 bytes per lane along a token's row
+    char* mine = bounce[wave];
+#pragma unroll
+    for (int m = 0; m < MB; m++)
+      *reinterpret_cast<uint2*>(mine + n * kDxBouncePitch + (16 * m + 4 * kg) * 2) =
+          make_uint2(pack_bf16(acc[m][0], acc[m][1]), pack_bf16(acc[m][2], acc[m][3]));
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wavefront's LDS writes are done
+    __builtin_amdgcn_wave_barrier();
+    constexpr int CPR = kDxColsPerWave / 8;   // 16-byte chunks per token row
+    constexpr int RPI = kWave / CPR;          // token rows per store instruction
+#pragma unroll
+    for (int it = 0; it < 16 / RPI; it++) {
+      const int r = RPI * it + lane / CPR, cc = lane % CPR;   // token row of the tile, chunk of 8 columns
+      if (t0 + r < t_end && cc < 2 * n_cb)
+        *reinterpret_cast<uint4*>(dx + (size_t)(t0 + r) * d + c0 + 8 * cc) = *reinterpret_cast<const uint4*>(mine + r * kDxBouncePitch + 16 * cc);
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // the read-back is complete before the next tile overwrites the buffer
+    __builtin_amdgcn_wave_barrier();
+    buf ^= 1;
+  }
+  }
+}
+
+// dW_r[e, c] (+)= sum over the S parts of partial[s][c][e]: the parts are the weight-gradient kernel's outputs for the
+// S pieces of the token range (columns of dx as rows, experts as columns, row pitch ldp, a multiple of 4); added in
+// part order.  A block sums 32 columns x up to 128 experts with 16-byte loads along the experts (all parts of an
+// element requested before the first add) and transposes through LDS, so that dW_r is written 128 bytes at a time.
+constexpr int kDwReduceCols = 32, kDwReduceExperts = 128;
+__global__ __launch_bounds__(256) void router_dw_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dw, int S, int E, int d,
+                                                               int ldp, int accumulate) {
+  __shared__ float tile[kDwReduceCols][kDwReduceExperts + 1];
+  const int c0 = blockIdx.x * kDwReduceCols, e0 = blockIdx.y * kDwReduceExperts;
+  const int ew = min(kDwReduceExperts, ldp - e0);   // experts (padded to 4) of this tile
+  const int quads = ew / 4;
+  const size_t part_stride = (size_t)d * ldp;
+  for (int i = threadIdx.x; i < kDwReduceCols * quads; i += 256) {
+    const int c = i / quads, q = i % quads;   // consecutive threads: consecutive 16 bytes of a column's row
+    r_f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (c0 + c < d) {
+      const float* src = partial + (size_t)(c0 + c) * ldp + e0 + 4 * q;
+      for (int p = 0; p < S; p += 8) {
+        r_f32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = (p + j < S) ? *reinterpret_cast<const r_f32x4*>(src + (size_t)(p + j) * part_stride) : r_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 8; j++) s += v[j];
+      }
+    }
+    tile[c][4 * q] = s.x; tile[c][4 * q + 1] = s.y; tile[c][4 * q + 2] = s.z; tile[c][4 * q + 3] = s.w;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < kDwReduceCols * ew; i += 256) {
+    const int e = i / kDwReduceCols, c = i % kDwReduceCols;   // consecutive threads: consecutive columns of an expert's row
+    if (c0 + c < d && e0 + e < E) {
+      float* dst = dw + (size_t)(e0 + e) * d + c0 + c;
+      *dst = accumulate ? *dst + tile[c][e] : tile[c][e];
+    }
+  }
+}
+
+void launch_router_prepare(hipStream_t st, const float* dlogits, const uint16_t* w_router, uint16_t* hi, uint16_t* lo, uint16_t* w_t,
+                           int32_t* offsets2, int32_t* part_order, uint32_t* zero_page, int T, int E, int Epad, int Ek, int d, int S,
+                           int part_rows) {
+  const long long n = max((long long)T * Epad, max((long long)d * (Ek / 8), 64LL));
+  MOE_LAUNCH("router_prepare", st, router_prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dlogits, w_router, hi, lo, w_t,
+             offsets2, part_order, zero_page, T, E, Epad, Ek, d, S, part_rows);
+}
+
+void launch_router_bwd_dx(hipStream_t st, const uint16_t* dl_hi, const uint16_t* dl_lo, const uint16_t* w_t, uint16_t* dx, int T, int d,
+                          int E, int Epad) {
+  // tokens per block: a multiple of 16, as large as still gives every CU a block
+  const unsigned col_groups = (unsigned)((d + kDxWaves * kDxColsPerWave - 1) / (kDxWaves * kDxColsPerWave));
+  int tpb = 1024;
+  while (tpb > 16 && (long long)((T + tpb - 1) / tpb) * col_groups < 256) tpb >>= 1;
+  const dim3 grid((unsigned)((T + tpb - 1) / tpb), col_groups), block(kDxWaves * kWave);
+  const int kgroups = (E + 31) / 32;
+  if (kgroups <= 1) MOE_LAUNCH("router_bwd_dx", st, (router_bwd_dx_kernel<1>), grid, block, 0, st, dl_hi, dl_lo, w_t, dx, T, d, Epad, tpb);
+  else if (kgroups <= 2) MOE_LAUNCH("router_bwd_dx", st, (router_bwd_dx_kernel<2>), grid, block, 0, st, dl_hi, dl_lo, w_t, dx, T, d, Epad, tpb);
+  else MOE_LAUNCH("router_bwd_dx", st, (router_bwd_dx_kernel<4>), grid, block, 0, st, dl_hi, dl_lo, w_t, dx, T, d, Epad, tpb);
+}
+
+void launch_router_dw_reduce(hipStream_t st, const float* partial, float* dw, int S, int E, int d, int ldp, int accumulate) {
+  const dim3 grid((unsigned)((d + kDwReduceCols - 1) / kDwReduceCols), (unsigned)((ldp + kDwReduceExperts - 1) / kDwReduceExperts));
+  MOE_LAUNCH("router_dw_reduce", st, router_dw_reduce_kernel, grid, dim3(256), 0, st, partial, dw, S, E, d, ldp, accumulate);
 }
 
 }  // namespace moe
