@@ -103,8 +103,9 @@ int moe_router_fwd(const moe_shape* shape, const uint16_t* x, const uint16_t* w_
 /* Derivative of moe_router_fwd:
  *   dx_router[t] = sum_e dlogits[t,e] w_router[e]     [T,d] bf16 out (one rounding)
  *   dw_router[e] = sum_t dlogits[t,e] x[t]            [E,d] fp32, overwritten (accumulate == 0) or added to
- * dlogits [T,E] fp32 in.  dlogits enters the matrix cores as a bf16 head plus a bf16 remainder (two passes), i.e.
- * with 16 significand bits; the products accumulate in fp32. */
+ * dlogits [T,E] fp32 in.  dlogits enters the matrix cores as a bf16 head plus a bf16 remainder (two products), i.e.
+ * with 16 significand bits; the products accumulate in fp32.  dw_router is the sum, in a fixed order, of the partial
+ * sums of up to 32 equal parts of the token range (deterministic). */
 int moe_router_bwd(const moe_shape* shape, const uint16_t* x, const uint16_t* w_router, const float* dlogits,
                    uint16_t* dx_router, float* dw_router, int accumulate, void* ws, size_t ws_bytes, void* stream);
 

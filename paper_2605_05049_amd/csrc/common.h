@@ -60,11 +60,26 @@ struct WsLayout {
   size_t router_offsets;    // 64 int32: {0, T}, {0, E} (one-segment "offsets" of the router's GEMMs) and the bounds of the parts of T
   size_t dl_hi, dl_lo;      // [T, Epad] bf16: head and remainder of the fp32 dlogits (Epad = E rounded up to 64)
   size_t w_router_t;        // [d, 128] bf16 at most: W_r transposed and zero-padded (router backward, E <= 128)
+  size_t router_dw_partial; // router_dw_parts() fp32 partial results [d, ldp] of dW_r^T
   size_t total;
 };
 
 inline int perm_num_blocks(long long N) { return (int)((N + kPermSlotsPerBlock - 1) / kPermSlotsPerBlock); }
 inline long long sched_max_tiles(const Dims& D) { return D.N / kMinTileRows + D.Et; }
+
+// The router's dW_r contraction over the T tokens is cut into S parts whose fp32 results [d, ldp] (ldp = E rounded up to
+// 4) are added afterwards: as many parts as give every CU a 256 x 128 tile, at most 32, at least 64 tokens each, and no
+// more than fit 128 MB (always at least one).
+inline size_t router_dw_part_bytes(const Dims& D) { return (size_t)D.d * round_up((size_t)D.E, 4) * sizeof(float); }
+inline int router_dw_parts(const Dims& D) {
+  const long long tiles = (long long)((D.d + 255) / 256) * ((D.E + 127) / 128);
+  long long S = (256 + tiles - 1) / tiles;
+  S = S < 32 ? S : 32;
+  const long long by_tokens = (D.T + 63) / 64, by_bytes = (long long)(((size_t)128 << 20) / router_dw_part_bytes(D));
+  S = S < by_tokens ? S : by_tokens;
+  S = S < by_bytes ? S : by_bytes;
+  return (int)(S < 1 ? 1 : S);
+}
 
 inline WsLayout ws_layout(const Dims& D) {
   WsLayout L;
@@ -96,7 +111,8 @@ inline WsLayout ws_layout(const Dims& D) {
   const size_t dl_bytes = round_up((size_t)D.T * round_up((size_t)D.E, 64) * sizeof(uint16_t) + 256, 256);
   L.dl_hi = off; off += dl_bytes;
   L.dl_lo = off; off += dl_bytes;
-  L.w_router_t = off; off += round_up((size_t)D.d * 128 * sizeof(uint16_t), 256);
+  L.w_router_t = off; off += D.E <= 128 ? round_up((size_t)D.d * 128 * sizeof(uint16_t), 256) : 0;
+  L.router_dw_partial = off; off += round_up((size_t)router_dw_parts(D) * router_dw_part_bytes(D), 256);
   L.total = off;
   return L;
 }

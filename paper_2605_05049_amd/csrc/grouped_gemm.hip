@@ -229,11 +229,10 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   // ---- block id -> tile ----
   int expert, p_row0 = 0, p_valid, q0_col, k_len;
   size_t krow0 = 0;
-  // Tail split (row-tile problems with a plain bf16 or fp32 output): when an XCD's last round of tiles would occupy at most half of its
+  // Tail split (row-tile problems with a plain bf16 output): when an XCD's last round of tiles would occupy at most half of its
   // 32 CUs, each of those tiles is cut along K into `split` parts that run side by side; a part writes its fp32
   // partial tile to the workspace and the part that arrives last adds them up (no part ever waits for another).
-  constexpr bool SPLITK = (KIND == 0 && (EPI == EPI_BF16 || EPI == EPI_F32));
-  constexpr bool NARROW = (KIND == 0 && EPI == EPI_F32);  // fp32-output row-tile problems are the router's: E rows or columns
+  constexpr bool SPLITK = (KIND == 0 && EPI == EPI_BF16);
   int split = 1, part = 0, part_slot = 0;
   int p_tile_idx;  // index of the tile along p
   if (KIND == 0) {
@@ -350,7 +349,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   // Each half of the shared panel is then requested right after the barrier by half of its users, and the requests
   // the other half makes half a step later find it in, or on its way to, the L2.  (Left out where it measured
   // slower or was not measured: the forward down projection and the router's skinny problems.)
-  constexpr bool ALTERNATE_Q = !(KIND == 0 && EPI == EPI_F32) && !(KIND == 0 && Q_RC && NQ == 1 && EPI == EPI_BF16);
+  constexpr bool ALTERNATE_Q = !(KIND == 0 && Q_RC && NQ == 1 && EPI == EPI_BF16);
   const int iwq = ALTERNATE_Q ? (wave ^ ((p_tile_idx & 1) << 2)) : wave;
   unsigned pvo[4], qvo[4];
 #pragma unroll
@@ -365,13 +364,13 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     const bool second = (NPASS == 2) && j >= nk_pass;
     const int k0 = (second ? j - nk_pass : j) * BK;
     issue_tile<P_RC, false, decltype(narrow_p)::value>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage, wave, lane);
-    issue_tile<Q_RC, NQ == 2, NARROW>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + Q_STAGE_OFFSET, iwq, lane);
+    issue_tile<Q_RC, NQ == 2>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + Q_STAGE_OFFSET, iwq, lane);
   };
   // the k-steps this block multiplies: all of them, or its part of a split tile
   const int kt_per = (nk + split - 1) / split;
   const int kt_begin = part * kt_per, kt_end = min(nk, kt_begin + kt_per);
   // (the first stage is requested before anything else is set up; rows a short tile does not have are clamped here)
-  if (kt_begin < kt_end) issue_as(std::integral_constant<bool, NARROW>{}, kt_begin, stage0);
+  if (kt_begin < kt_end) issue_as(std::false_type{}, kt_begin, stage0);
   // Height class of the tile: each of the two wavefronts along p multiplies PB blocks of 32 rows (4, 2 or 1), so a
   // ragged last row tile of an expert issues MFMAs and row loads for its class (256, 128 or 64 rows) only.
   auto run = [&](auto pb_c) __attribute__((always_inline)) {
@@ -387,7 +386,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     }
   };
   auto issue = [&](int j, char* stage) __attribute__((always_inline)) {
-    issue_as(std::integral_constant<bool, NARROW || PB < 4>{}, j, stage);
+    issue_as(std::integral_constant<bool, (PB < 4)>{}, j, stage);
     issue_tall(j, stage);
   };
   if (kt_begin < kt_end) issue_tall(kt_begin, stage0);   // (the rest of the first stage was requested above)
@@ -444,7 +443,6 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   __syncthreads();                             // every wavefront has finished reading the stages
   char* wlds = ((wave < 4) ? stage0 : stage1) + (wave & 3) * 16384;
   const int q_base = wq * W;                   // first q of this wavefront inside the output's tile
-  const bool f32_vector_ok = (A.c_ld & 3) == 0;  // 16-byte fp32 stores need rows that start on 16-byte boundaries
   if (SPLITK && split > 1) {
     // ---- a part of a split tile: fp32 partial tile -> workspace, then whoever arrives last reduces
     float* mine = A.partial + (size_t)part_slot * (TALL * TILE);
@@ -498,13 +496,8 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
         const f32x4 x1 = load_agent_f4(parts + (size_t)sp * (TALL * TILE) + p * TILE + q + 4);
         x[0] += x0.x; x[1] += x0.y; x[2] += x0.z; x[3] += x0.w; x[4] += x1.x; x[5] += x1.y; x[6] += x1.z; x[7] += x1.w;
       }
-      if (EPI == EPI_F32) {
-        float* dst = A.f0 + (size_t)expert * A.f_expert_stride + (size_t)(p_row0 + p) * A.c_ld + q0_col + q;
-        for (int i = 0; i < 8 && q + i < q_valid; i++) dst[i] = A.accumulate ? dst[i] + x[i] : x[i];
-      } else {
-        *reinterpret_cast<uint4*>(A.c0 + (size_t)(p_row0 + p) * A.c_ld + q0_col + q) =
-            make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
-      }
+      *reinterpret_cast<uint4*>(A.c0 + (size_t)(p_row0 + p) * A.c_ld + q0_col + q) =
+          make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
     }
     return;
   }
@@ -541,16 +534,13 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
               v.x += v1.x; v.y += v1.y; v.z += v1.z; v.w += v1.w;
             }
             float* dst = (n == 0 ? A.f0 : A.f1) + o;
-            if (!NARROW || (f32_vector_ok && q_base + q + 4 <= q_valid)) {   // (d_model, d_ffn are multiples of 64)
-              if (A.accumulate) {
-                const float4 old = *reinterpret_cast<const float4*>(dst);
-                v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
-              }
-              *reinterpret_cast<float4*>(dst) = v;
-            } else {  // a row pitch or a width that is not a multiple of 4 (router logits with odd E): element-wise
-              const float e4[4] = {v.x, v.y, v.z, v.w};
-              for (int i = 0; i < 4 && q_base + q + i < q_valid; i++) dst[i] = A.accumulate ? dst[i] + e4[i] : e4[i];
+            // (16-byte stores: the row pitch is a multiple of 4 and a row has room for whole groups of 4: d_model and
+            // d_ffn are multiples of 64, the router's partial results are padded to 4)
+            if (A.accumulate) {
+              const float4 old = *reinterpret_cast<const float4*>(dst);
+              v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
             }
+            *reinterpret_cast<float4*>(dst) = v;
           }
         }
       }
@@ -670,7 +660,7 @@ template <int KIND, bool P_RC, bool Q_RC, int NQ, int NPASS, int EPI>
 static int launch_gemm(const char* label, const GemmArgs& A, long long max_blocks, hipStream_t st) {
   auto kern = grouped_gemm_kernel<KIND, P_RC, Q_RC, NQ, NPASS, EPI>;
   // bf16-output row-tile problems may cut the tiles of an XCD's last round into up to 32 parts in all
-  const long long per_xcd = (max_blocks + kNumXcd - 1) / kNumXcd + ((KIND == 0 && (EPI == EPI_BF16 || EPI == EPI_F32)) ? kCusPerXcd : 0);
+  const long long per_xcd = (max_blocks + kNumXcd - 1) / kNumXcd + ((KIND == 0 && EPI == EPI_BF16) ? kCusPerXcd : 0);
   const long long grid = per_xcd * kNumXcd;
   if (max_blocks <= 0) return MOE_OK;
   MOE_LAUNCH(label, st, kern, dim3((unsigned)grid), dim3(NTHREADS), 0, st, A);
@@ -825,25 +815,19 @@ extern "C" int moe_router_bwd(const moe_shape* shape, const uint16_t* x, const u
   const bool skinny_dx = D.E <= 128;                          // (the dx kernel keeps W_r^T for 128 experts in registers)
   const int Ek = D.E <= 32 ? 32 : (D.E <= 64 ? 64 : 128);    // experts padded to the dx kernel's k-groups
   uint16_t* w_t = reinterpret_cast<uint16_t*>(wsb + L.w_router_t);
-  float* partial = reinterpret_cast<float*>(wsb + L.splitk_partial);
+  float* partial = reinterpret_cast<float*>(wsb + L.router_dw_partial);
   // dW_r: the token range is cut into S parts, each a "segment" of the weight-gradient kernel with its own fp32 output
-  // [d, ldp] in the partial-tile area; S gives every CU a tile if the area allows
+  // [d, ldp] in the workspace
   const int n_p_tiles = (int)((D.d + TILE - 1) / TILE), n_q_tiles = (int)((D.E + 127) / 128);
   const int ldp = (int)round_up((size_t)D.E, 4);
-  const size_t part_bytes = (size_t)D.d * ldp * sizeof(float);
-  const size_t area_bytes = (size_t)kSplitParts * 320 * 256 * sizeof(float);
-  long long S = (256 + (long long)n_p_tiles * n_q_tiles - 1) / ((long long)n_p_tiles * n_q_tiles);
-  S = std::min<long long>(S, 32);
-  S = std::min<long long>(S, (long long)(area_bytes / part_bytes));
-  S = std::min<long long>(S, (D.T + 63) / 64);
-  if (S < 1) return MOE_ERR_WORKSPACE;   // (d * E beyond 21 M elements: not a router)
+  const int S = router_dw_parts(D);
   const int part_rows = (int)round_up((size_t)((D.T + S - 1) / S), 64);
   launch_router_prepare(st, dlogits, w_router, dl_hi, dl_lo, skinny_dx ? w_t : nullptr, offs, sched + 64 + 2 * max_tiles, zero_page, (int)D.T,
                         (int)D.E, Epad, Ek, (int)D.d, (int)S, part_rows);
   GemmArgs A = {};
   A.sched = sched; A.max_tiles = max_tiles; A.Et = 1; A.accumulate = 0;
   A.zero_page = reinterpret_cast<const uint16_t*>(zero_page);
-  A.partial = partial; A.counters = counters;
+  A.partial = reinterpret_cast<float*>(wsb + L.splitk_partial); A.counters = counters;
   if (skinny_dx) {
     launch_router_bwd_dx(st, dl_hi, dl_lo, w_t, dx_router, (int)D.T, (int)D.d, (int)D.E, Epad);
   } else {

@@ -170,15 +170,17 @@ __global__ __launch_bounds__(256) void router_prepare_kernel(const float* __rest
 }
 
 // dx_router[t, c] = sum_e dlogits[t, e] W_r[e, c] for E <= 128: T x d x E with E small, so its time is the time to
-// write dx once.  A block of 8 wavefronts owns `tokens_per_block` tokens and 1024 columns (2 KB of a token's row: narrower
-// blocks measured slower); a wavefront keeps the W_r^T fragments of its 128 columns (8 blocks of 16 columns x KG groups
-// of 32 experts) in registers for the whole block.
-// Per 16 tokens the block stages the head and the remainder of dlogits in LDS once (one 16-byte load per thread,
-// double-buffered, chunk positions XOR-swizzled with the token so that the fragment reads are conflict-free), every
-// wavefront multiplies (MFMA 16x16x32, columns as rows of the result so that a lane ends up with 4 consecutive
-// columns of a token), and bounces its 16 x 128 bf16 results through LDS to store 256 contiguous bytes per token.
-constexpr int kDxWaves = 8;
-constexpr int kDxColsPerWave = 128;
+// write dx once.  A block of 16 wavefronts owns `tokens_per_block` tokens and 1024 columns (2 KB of a token's row:
+// narrower blocks measured slower); a wavefront keeps the W_r^T fragments of its 64 columns (4 blocks of 16 columns x
+// KG groups of 32 experts) in registers for the whole block.  Per 64 tokens the block stages the head and the
+// remainder of dlogits in LDS once (16-byte loads, the next 64 tokens' pieces in flight in registers, chunk positions
+// XOR-swizzled with the token so that the fragment reads are conflict-free); between two such barriers every
+// wavefront works through four tiles of 16 tokens at its own pace: multiply (MFMA 16x16x32, columns as rows of the
+// result so that a lane ends up with 4 consecutive columns of a token), bounce the 16 x 64 bf16 results through its
+// own LDS patch, store 128 contiguous bytes per token, so that one wavefront's stores overlap another's multiplies.
+constexpr int kDxWaves = 16;
+constexpr int kDxColsPerWave = 64;
+constexpr int kDxTokensPerStage = 64;
 constexpr int kDxBouncePitch = kDxColsPerWave * 2 + 16;   // bytes per staged token row (the +16 spreads the banks)
 
 template <int KG>
@@ -188,7 +190,11 @@ __global__ __launch_bounds__(kDxWaves * kWave) void router_bwd_dx_kernel(const u
   constexpr int Ek = 32 * KG;                  // experts padded to whole k-groups
   constexpr int CH = 4 * KG;                   // 16-byte chunks per staged row
   constexpr int ROWB = Ek * 2;                 // bytes per staged row
-  __shared__ __attribute__((aligned(16))) char dl_tile[2][2 * 16 * ROWB];       // [buffer][hi | lo][token][expert]
+  constexpr int TS = kDxTokensPerStage;
+  constexpr int NTHR = kDxWaves * kWave;
+  constexpr int ITEMS = 2 * TS * CH;           // 16-byte pieces of a stage (head and remainder)
+  constexpr int PER = (ITEMS + NTHR - 1) / NTHR;   // ... per thread
+  __shared__ __attribute__((aligned(16))) char dl_tile[2][2 * TS * ROWB];       // [buffer][hi | lo][token][expert]
   __shared__ __attribute__((aligned(16))) char bounce[kDxWaves][16 * kDxBouncePitch];
   const int lane = threadIdx.x % kWave;
   const int wave = threadIdx.x / kWave;
@@ -208,43 +214,49 @@ __global__ __launch_bounds__(kDxWaves * kWave) void router_bwd_dx_kernel(const u
     for (int g = 0; g < KG; g++) wf[m][g] = *reinterpret_cast<const r_bf16x8*>(w_t + (size_t)c * Ek + 32 * g + 8 * kg);
   }
 
-  // staging role of this thread: tensor (hi | lo), token row and chunk of the 16-token tile (threads past the tile idle)
-  const int s_part = threadIdx.x / (16 * CH);
-  const int s_row = (threadIdx.x / CH) % 16, s_ch = threadIdx.x % CH;
-  const bool stager = threadIdx.x < 2 * 16 * CH;
-  const uint16_t* s_src = (s_part == 0 ? dl_hi : dl_lo) + 8 * s_ch;
-  const int s_dst = (s_part * 16 + s_row) * ROWB + ((s_ch ^ ((s_row * KG) >> 2)) & (CH - 1)) * 16;
-  auto fetch = [&](int t0) -> uint4 {
-    const int t = min(t0 + s_row, T - 1);   // rows past the end are clamped (never stored)
-    return stager ? *reinterpret_cast<const uint4*>(s_src + (size_t)t * Epad) : make_uint4(0u, 0u, 0u, 0u);
+  // staging: piece i of a stage = tensor i / (TS CH), token row (i / CH) % TS, chunk i % CH; thread t takes pieces
+  // t, t + NTHR, ...
+  uint4 staged[PER];
+  auto fetch = [&](int t0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < PER; k++) {
+      const int i = threadIdx.x + k * NTHR;
+      const int part = i / (TS * CH), row = (i / CH) % TS, ch = i % CH;
+      const int t = min(t0 + row, T - 1);   // rows past the end are clamped (never stored)
+      staged[k] = (i < ITEMS) ? *reinterpret_cast<const uint4*>((part == 0 ? dl_hi : dl_lo) + (size_t)t * Epad + 8 * ch) : make_uint4(0u, 0u, 0u, 0u);
+    }
   };
-  // the next four tiles' pieces are in flight in registers (a tile's multiply is much shorter than a load's latency)
-  uint4 staged[4];
+  auto publish = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
-  for (int j = 0; j < 4; j++) staged[j] = (t_begin + 16 * j < t_end) ? fetch(t_begin + 16 * j) : make_uint4(0u, 0u, 0u, 0u);
-  int buf = 0;
-  for (int t4 = t_begin; t4 < t_end; t4 += 64) {
-#pragma unroll
-  for (int j = 0; j < 4; j++) {
-    const int t0 = t4 + 16 * j;
-    if (t0 >= t_end) break;   // (uniform over the block)
-    if (stager) *reinterpret_cast<uint4*>(&dl_tile[buf][s_dst]) = staged[j];
-    __syncthreads();
-    if (t0 + 64 < t_end) staged[j] = fetch(t0 + 64);
-    r_f32x4 acc[MB];
+    for (int k = 0; k < PER; k++) {
+      const int i = threadIdx.x + k * NTHR;
+      const int part = i / (TS * CH), row = (i / CH) % TS, ch = i % CH;
+      if (i < ITEMS) *reinterpret_cast<uint4*>(&dl_tile[b][(part * TS + row) * ROWB + ((ch ^ (((row & 15) * KG) >> 2)) & (CH - 1)) * 16]) = staged[k];
+    }
+  };
+  r_f32x4 acc[MB];
+  auto multiply = [&](int b, int j) __attribute__((always_inline)) {   // tile j of stage b
 #pragma unroll
     for (int m = 0; m < MB; m++) acc[m] = r_f32x4{0.f, 0.f, 0.f, 0.f};
+    // 2 KG fragment reads (remainder first, then the head), each one group ahead of the MFMAs that use it
+    auto frag = [&](int sidx) __attribute__((always_inline)) -> r_bf16x8 {
+      const int part = 1 - sidx / KG, g = sidx % KG;
+      const int ch = ((4 * g + kg) ^ ((n * KG) >> 2)) & (CH - 1);
+      return *reinterpret_cast<const r_bf16x8*>(&dl_tile[b][(part * TS + 16 * j + n) * ROWB + ch * 16]);
+    };
+    r_bf16x8 df = frag(0);
 #pragma unroll
-    for (int part = 1; part >= 0; part--) {   // remainder first, then the head
+    for (int sidx = 0; sidx < 2 * KG; sidx++) {
+      const r_bf16x8 nxt = frag(min(sidx + 1, 2 * KG - 1));
+      __builtin_amdgcn_sched_barrier(0);   // (keeps the read above the MFMAs it is meant to overlap)
 #pragma unroll
-      for (int g = 0; g < KG; g++) {
-        const int ch = ((4 * g + kg) ^ ((n * KG) >> 2)) & (CH - 1);
-        const r_bf16x8 df = *reinterpret_cast<const r_bf16x8*>(&dl_tile[buf][(part * 16 + n) * ROWB + ch * 16]);
-#pragma unroll
-        for (int m = 0; m < MB; m++) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[m][g], df, acc[m], 0, 0, 0);
-      }
+      for (int m = 0; m < MB; m++) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[m][sidx % KG], df, acc[m], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      df = nxt;
     }
-    // acc[m][i] = dx[t0 + n][c0 + 16 m + 4 kg + i]: to LDS as bf16, back as 16 bytes per lane along a token's row
+  };
+  // acc[m][i] = dx[t0 + n][c0 + 16 m + 4 kg + i]: to LDS as bf16, back as 16 bytes per lane along a token's row
+  auto store_tile = [&](int t0) __attribute__((always_inline)) {
     char* mine = bounce[wave];
 #pragma unroll
     for (int m = 0; m < MB; m++)
@@ -260,10 +272,22 @@ __global__ __launch_bounds__(kDxWaves * kWave) void router_bwd_dx_kernel(const u
       if (t0 + r < t_end && cc < 2 * n_cb)
         *reinterpret_cast<uint4*>(dx + (size_t)(t0 + r) * d + c0 + 8 * cc) = *reinterpret_cast<const uint4*>(mine + r * kDxBouncePitch + 16 * cc);
     }
-    __builtin_amdgcn_s_waitcnt(0xC07F);   // the read-back is complete before the next tile overwrites the buffer
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // the read-back is complete before the next tile overwrites the patch
     __builtin_amdgcn_wave_barrier();
-    buf ^= 1;
-  }
+  };
+  fetch(t_begin);
+  int buf = 0;
+  for (int ts = t_begin; ts < t_end; ts += TS, buf ^= 1) {
+    publish(buf);
+    __syncthreads();   // (a stage is overwritten two barriers after it was published: everyone has finished with it)
+    if (ts + TS < t_end) fetch(ts + TS);
+#pragma unroll
+    for (int j = 0; j < TS / 16; j++) {
+      if (ts + 16 * j < t_end) {
+        multiply(buf, j);
+        store_tile(ts + 16 * j);
+      }
+    }
   }
 }
 
@@ -314,10 +338,10 @@ void launch_router_prepare(hipStream_t st, const float* dlogits, const uint16_t*
 
 void launch_router_bwd_dx(hipStream_t st, const uint16_t* dl_hi, const uint16_t* dl_lo, const uint16_t* w_t, uint16_t* dx, int T, int d,
                           int E, int Epad) {
-  // tokens per block: a multiple of 16, as large as still gives every CU a block
+  // tokens per block: a multiple of a stage's 64, as large as still gives every CU a block
   const unsigned col_groups = (unsigned)((d + kDxWaves * kDxColsPerWave - 1) / (kDxWaves * kDxColsPerWave));
   int tpb = 1024;
-  while (tpb > 16 && (long long)((T + tpb - 1) / tpb) * col_groups < 256) tpb >>= 1;
+  while (tpb > kDxTokensPerStage && (long long)((T + tpb - 1) / tpb) * col_groups < 256) tpb >>= 1;
   const dim3 grid((unsigned)((T + tpb - 1) / tpb), col_groups), block(kDxWaves * kWave);
   const int kgroups = (E + 31) / 32;
   if (kgroups <= 1) MOE_LAUNCH("router_bwd_dx", st, (router_bwd_dx_kernel<1>), grid, block, 0, st, dl_hi, dl_lo, w_t, dx, T, d, Epad, tpb);
