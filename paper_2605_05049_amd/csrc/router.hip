@@ -27,7 +27,8 @@ constexpr int kRouterExpertTile = 128;   // experts per block (grid.y walks the 
 template <int TB, int NEB>
 __global__ __launch_bounds__(kRouterWaves * kWave) void router_fwd_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router,
                                                                          float* __restrict__ logits, int T, int E, int d) {
-  __shared__ float part_sum[kRouterWaves][16 * 16];   // one 16 x 16 block of partial logits per wavefront
+  constexpr int NBLK = (NEB * TB < 16) ? NEB * TB : 16;   // 16 x 16 blocks of partial logits that meet in LDS at a time
+  __shared__ float part_sum[kRouterWaves][NBLK][16 * 16];   // (up to 128 KB)
   const int lane = threadIdx.x % kWave;
   const int wave = threadIdx.x / kWave;
   const int n = lane & 15, kg = lane >> 4;            // token (or expert) inside a block of 16, group of 8 k
@@ -93,24 +94,27 @@ __global__ __launch_bounds__(kRouterWaves * kWave) void router_fwd_kernel(const 
     });
   }
 
-  // the 8 parts of K meet in LDS, one 16 x 16 block at a time, and are added in part order; thread i of the block
-  // then owns logit (token i / 16, expert i % 16) of the block: 16 consecutive experts of a row per 16 threads
-  const int rt = threadIdx.x >> 4, re = threadIdx.x & 15;
+  // the 8 parts of K meet in LDS, NBLK blocks of 16 x 16 at a time (block q = m TB + b), and are added in part order;
+  // item i of a pass is logit (token (i % 256) / 16, expert i % 16) of block i / 256: 16 consecutive experts of a row
+  // per 16 threads
+  constexpr int NPASS = (NEB * TB + NBLK - 1) / NBLK;
 #pragma unroll
-  for (int m = 0; m < NEB; m++) {
-    if (e0 + 16 * m >= E) break;   // (uniform over the block)
+  for (int pass = 0; pass < NPASS; pass++) {
+    if (pass > 0) __syncthreads();   // the previous pass has been read
 #pragma unroll
-    for (int b = 0; b < TB; b++) {
-      *reinterpret_cast<r_f32x4*>(&part_sum[wave][n * 16 + 4 * kg]) = acc[m][b];   // [token][expert]
-      __syncthreads();
-      if (threadIdx.x < 256) {
-        float s = 0.f;
+    for (int j = 0; j < NBLK; j++) {
+      const int q = pass * NBLK + j;
+      if (q < NEB * TB) *reinterpret_cast<r_f32x4*>(&part_sum[wave][j][n * 16 + 4 * kg]) = acc[q / TB][q % TB];   // [token][expert]
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < NBLK * 256; i += kRouterWaves * kWave) {
+      const int j = i >> 8, idx = i & 255, q = pass * NBLK + j;
+      if (q >= NEB * TB) break;
+      float sum = 0.f;
 #pragma unroll
-        for (int p = 0; p < kRouterWaves; p++) s += part_sum[p][threadIdx.x];
-        const int t = t0 + 16 * b + rt, e = e0 + 16 * m + re;
-        if (t < T && e < E) logits[(size_t)t * E + e] = s;
-      }
-      __syncthreads();
+      for (int p = 0; p < kRouterWaves; p++) sum += part_sum[p][j][idx];
+      const int t = t0 + 16 * (q % TB) + (idx >> 4), e = e0 + 16 * (q / TB) + (idx & 15);
+      if (t < T && e < E) logits[(size_t)t * E + e] = sum;
     }
   }
 }

@@ -30,8 +30,11 @@ def router_case(T, d, E, seed):
 
 
 ROUTER_SHAPES = [
-    # T, d, E: one tile, ragged token tail, E not a multiple of 4 / of 8, E over one 256-wide tile, many tiles (K split)
+    # T, d, E: one tile, ragged token tail, E not a multiple of 4 / of 8, E over 128 (dx on the grouped GEMM kernel), many tiles
     (256, 512, 8), (777, 256, 60), (300, 128, 7), (1000, 192, 300), (4096, 1024, 128), (64, 64, 1), (2500, 2048, 16),
+    # every expert-group count of the skinny dx kernel (32, 64, 128 padded experts) with ragged E, more columns than one
+    # block's 1024, fewer tokens than one stage of 64
+    (500, 320, 96), (130, 1280, 33), (40, 2112, 32),
     # the router of the two workloads bench.py times it on, at full size
     (4096, 4096, 8), (16384, 4096, 128),
 ]
