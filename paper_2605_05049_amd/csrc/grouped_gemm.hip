@@ -567,7 +567,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
             const float u[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
             float h[8];
 #pragma unroll
-            for (int i = 0; i < 8; i++) h[i] = x[i] / (1.0f + __expf(-x[i])) * u[i];
+            for (int i = 0; i < 8; i++) h[i] = x[i] * __builtin_amdgcn_rcpf(1.0f + __expf(-x[i])) * u[i];   // (rcp: 1 ulp, bf16 result)
             *reinterpret_cast<uint4*>(A.c0 + o) =
                 make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
             *reinterpret_cast<uint4*>(A.c1 + o) =
@@ -582,7 +582,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
             float dg[8], du[8], h[8];
 #pragma unroll
             for (int i = 0; i < 8; i++) {
-              const float sg = 1.0f / (1.0f + __expf(-g[i]));
+              const float sg = __builtin_amdgcn_rcpf(1.0f + __expf(-g[i]));   // (rcp: 1 ulp, bf16 results)
               const float sl = g[i] * sg;
               h[i] = sl * u[i];
               du[i] = x[i] * sl;
