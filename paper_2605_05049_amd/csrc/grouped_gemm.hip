@@ -427,9 +427,52 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[a], pf[b], acc[a][b], 0, 0, 0);
     }
   };
-  for (int kt = kt_begin; kt < kt_end; kt += 2) {
-    k_step(stage0, stage1, kt);
-    if (kt + 1 < kt_end) k_step(stage1, stage0, kt + 1);
+  // Tiles of at most 64 rows (PB == 1) multiply little per step and are bound by the latency of their loads, and
+  // their P operand needs 8 KB of a stage's 40: they run a ring of three slots, two steps ahead instead of one.
+  //   slot 0: P at stage0, Q at stage0 + 40 KB (the layout of the first stage requested above)
+  //   slot 1: P at stage1, Q at stage1 + 40 KB
+  //   slot 2: P at stage1 + 8 KB, Q at stage0 + 8 KB (rows 64.. of the other slots' P areas, which these tiles never read)
+  // Every wavefront issues one P instruction (rows 8 w .. 8 w + 7, clamped onto the tile's last row) and its four Q
+  // instructions per step: 5 loads, the same for all, so that "all but the youngest step" is vmcnt(5).
+  if constexpr (PB == 1) {
+    const unsigned pvo1 = load_offset<P_RC, false>(P, wave, lane);
+    auto issue1 = [&](int j, char* p_dst, char* q_dst) __attribute__((always_inline)) {
+      const bool second = (NPASS == 2) && j >= nk_pass;
+      const int k0 = (second ? j - nk_pass : j) * BK;
+      direct_load16(P.base0 + (second ? p_pass_delta : (ptrdiff_t)0) + k0, pvo1, p_dst + wave * 1024);
+      issue_tile<Q_RC, NQ == 2>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, q_dst, iwq, lane);
+    };
+    auto ring_step = [&](const char* p_lds, const char* q_lds, char* p_fill, char* q_fill, int kt) {
+      if (kt + 1 < kt_end) __builtin_amdgcn_s_waitcnt(0x0F75);  // vmcnt(5): all but the 5 loads of step kt + 1
+      else __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();   // step kt has landed for everyone; everyone is done with step kt - 1, whose slot step kt + 2 takes
+      if (late && kt + 2 < kt_end) issue1(kt + 2, p_fill, q_fill);
+#pragma unroll
+      for (int kk = 0; kk < BK; kk += 16) {
+        if (kk == MOE_EARLY_ISSUE_AT) {
+          __builtin_amdgcn_sched_barrier(0);
+          if (!late && kt + 2 < kt_end) issue1(kt + 2, p_fill, q_fill);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        const bf16x8 q0f = read_frag<Q_RC>(q_lds, qr0, kk, lane), q1f = read_frag<Q_RC>(q_lds, qr1, kk, lane);
+        const bf16x8 p0f = read_frag<P_RC>(p_lds, wp, kk, lane);
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q0f, p0f, acc[0][0], 0, 0, 0);
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q1f, p0f, acc[1][0], 0, 0, 0);
+      }
+    };
+    char* const rp[3] = {stage0, stage1, stage1 + 8192};
+    char* const rq[3] = {stage0 + Q_STAGE_OFFSET, stage1 + Q_STAGE_OFFSET, stage0 + 8192};
+    if (kt_begin + 1 < kt_end) issue1(kt_begin + 1, rp[1], rq[1]);
+    for (int kt = kt_begin; kt < kt_end; kt += 3) {
+      ring_step(rp[0], rq[0], rp[2], rq[2], kt);
+      if (kt + 1 < kt_end) ring_step(rp[1], rq[1], rp[0], rq[0], kt + 1);
+      if (kt + 2 < kt_end) ring_step(rp[2], rq[2], rp[1], rq[1], kt + 2);
+    }
+  } else {
+    for (int kt = kt_begin; kt < kt_end; kt += 2) {
+      k_step(stage0, stage1, kt);
+      if (kt + 1 < kt_end) k_step(stage1, stage0, kt + 1);
+    }
   }
 
   // ---- epilogue.  acc[a][b][v] holds  p = wp + 32b + lane%32,  q (inside the output's tile) =
