@@ -54,6 +54,15 @@ constexpr int STAGE_BYTES = Q_STAGE_OFFSET + OPERAND_BYTES;  // P + Q = 72 KB
                                                 // two stages = 144 KB of the 160 KB of LDS
 constexpr int kNumXcd = 8;
 constexpr int kCusPerXcd = 32;
+// A tile is cut along K only if it has at least MOE_SPLIT_MIN_STEPS k-steps, into parts of at least MOE_SPLIT_PART_STEPS
+// (writing a part's fp32 tile and adding the parts costs about as much as 20 k-steps: a 32-step tile cut in four
+// measured 4 % slower than left whole).
+#ifndef MOE_SPLIT_MIN_STEPS
+#define MOE_SPLIT_MIN_STEPS 48
+#endif
+#ifndef MOE_SPLIT_PART_STEPS
+#define MOE_SPLIT_PART_STEPS 16
+#endif
 #ifndef MOE_EARLY_ISSUE_AT
 #define MOE_EARLY_ISSUE_AT 32   // k offset inside a step at which wavefronts 0..3 request their share of the next stage
 #endif
@@ -79,7 +88,7 @@ struct GemmArgs {
   int accumulate;
   const uint16_t* zero_page;  // 256 zeroed bytes: source of k-rows past the end of a ragged K
   float* partial;             // [kSplitParts][256][256] fp32: partial tiles of a split K range
-  int32_t* counters;          // [kSplitCounters], zeroed by the schedule kernel: parts of a split tile that have arrived
+  int32_t* counters;          // [kSplitCounters], zeroed by the schedule kernel and again by each tile's reducing part: parts of a split tile that have arrived
   // outputs
   uint16_t* c0; uint16_t* c1; uint16_t* c2; size_t c_ld;   // bf16 outputs (row-major, ld = q_dim)
   const uint16_t* g_in; const uint16_t* u_in;              // saved G, U for the d(SwiGLU) epilogue
@@ -168,12 +177,19 @@ __device__ __forceinline__ void issue_tile(const unsigned (&voff)[4], const Tile
   }
 }
 
-// 16 bytes that another CU has written during this launch: read at agent scope, so that this CU's vector L1 is
-// bypassed whatever it holds (the partial tiles of a split K range).
-__device__ __forceinline__ f32x4 load_agent_f4(const float* p) {
-  f32x4 v;
-  asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
-  return v;
+// 8 x 16 bytes that other CUs have written during this launch (32 bytes at each of four addresses): read at agent
+// scope, so that this CU's vector L1 is bypassed whatever it holds (the partial tiles of a split K range).  One
+// statement issues the eight loads and waits for them, so the compiler never sees a register whose load is in flight.
+__device__ __forceinline__ void load8_agent(f32x4 (&v)[8], const float* p0, const float* p1, const float* p2, const float* p3) {
+  asm volatile(
+      "global_load_dwordx4 %0, %8, off sc1\n\tglobal_load_dwordx4 %1, %8, off offset:16 sc1\n\t"
+      "global_load_dwordx4 %2, %9, off sc1\n\tglobal_load_dwordx4 %3, %9, off offset:16 sc1\n\t"
+      "global_load_dwordx4 %4, %10, off sc1\n\tglobal_load_dwordx4 %5, %10, off offset:16 sc1\n\t"
+      "global_load_dwordx4 %6, %11, off sc1\n\tglobal_load_dwordx4 %7, %11, off offset:16 sc1\n\t"
+      "s_waitcnt vmcnt(0)"
+      : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+      : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+      : "memory");
 }
 
 // MFMA operand fragment: 32 r-values x 16 k-values; lane l gets r = r0 + l%32, k = kk + 8*(l/32) .. +7.
@@ -229,10 +245,10 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   // ---- block id -> tile ----
   int expert, p_row0 = 0, p_valid, q0_col, k_len;
   size_t krow0 = 0;
-  // Tail split (row-tile problems with a plain bf16 output): when an XCD's last round of tiles would occupy at most half of its
+  // Tail split (row-tile problems with one output tile per block): when an XCD's last round of tiles would occupy at most half of its
   // 32 CUs, each of those tiles is cut along K into `split` parts that run side by side; a part writes its fp32
   // partial tile to the workspace and the part that arrives last adds them up (no part ever waits for another).
-  constexpr bool SPLITK = (KIND == 0 && EPI == EPI_BF16);
+  constexpr bool SPLITK = (KIND == 0 && NQ == 1);   // (the SwiGLU forward, with two output tensors per tile, measured no gain)
   int split = 1, part = 0, part_slot = 0;
   int p_tile_idx;  // index of the tile along p
   if (KIND == 0) {
@@ -254,8 +270,8 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     if (SPLITK) {
       const int rem = (int)(cnt % kCusPerXcd);
       const int nk_all = ((A.k_dim + BK - 1) / BK) * NPASS;
-      if (rem > 0 && rem <= kCusPerXcd / 2 && nk_all >= 16) {
-        split = min(min(kCusPerXcd / rem, 8), nk_all / 8);
+      if (rem > 0 && rem <= kCusPerXcd / 2 && nk_all >= MOE_SPLIT_MIN_STEPS) {
+        split = min(min(kCusPerXcd / rem, 8), nk_all / MOE_SPLIT_PART_STEPS);
         full = cnt - rem;
       }
     }
@@ -486,8 +502,46 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   __syncthreads();                             // every wavefront has finished reading the stages
   char* wlds = ((wave < 4) ? stage0 : stage1) + (wave & 3) * 16384;
   const int q_base = wq * W;                   // first q of this wavefront inside the output's tile
+  // 8 consecutive outputs of a row: x (and, for the SwiGLU forward, the matching values y of the second tensor) ->
+  // the kernel's bf16 outputs at element offset o
+  auto emit8 = [&](size_t o, const float (&x)[8], const float (&y)[8]) __attribute__((always_inline)) {
+    if (EPI == EPI_BF16) {
+      *reinterpret_cast<uint4*>(A.c0 + o) =
+          make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+    } else if (EPI == EPI_SWIGLU) {  // x = G, y = U
+      float h[8];
+#pragma unroll
+      for (int i = 0; i < 8; i++) h[i] = x[i] * __builtin_amdgcn_rcpf(1.0f + __expf(-x[i])) * y[i];   // (rcp: 1 ulp, bf16 result)
+      *reinterpret_cast<uint4*>(A.c0 + o) =
+          make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+      *reinterpret_cast<uint4*>(A.c1 + o) =
+          make_uint4(pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3]), pack_bf16(y[4], y[5]), pack_bf16(y[6], y[7]));
+      *reinterpret_cast<uint4*>(A.c2 + o) =
+          make_uint4(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]), pack_bf16(h[4], h[5]), pack_bf16(h[6], h[7]));
+    } else if (EPI == EPI_DSWIGLU) {  // x = dH; read saved G, U; write dG, dU, H
+      const uint4 gi = *reinterpret_cast<const uint4*>(A.g_in + o);
+      const uint4 ui = *reinterpret_cast<const uint4*>(A.u_in + o);
+      const float g[8] = {bf16lo(gi.x), bf16hi(gi.x), bf16lo(gi.y), bf16hi(gi.y), bf16lo(gi.z), bf16hi(gi.z), bf16lo(gi.w), bf16hi(gi.w)};
+      const float u[8] = {bf16lo(ui.x), bf16hi(ui.x), bf16lo(ui.y), bf16hi(ui.y), bf16lo(ui.z), bf16hi(ui.z), bf16lo(ui.w), bf16hi(ui.w)};
+      float dg[8], du[8], h[8];
+#pragma unroll
+      for (int i = 0; i < 8; i++) {
+        const float sg = __builtin_amdgcn_rcpf(1.0f + __expf(-g[i]));   // (rcp: 1 ulp, bf16 results)
+        const float sl = g[i] * sg;
+        h[i] = sl * u[i];
+        du[i] = x[i] * sl;
+        dg[i] = x[i] * u[i] * (sg * (1.0f + g[i] * (1.0f - sg)));
+      }
+      *reinterpret_cast<uint4*>(A.c0 + o) =
+          make_uint4(pack_bf16(dg[0], dg[1]), pack_bf16(dg[2], dg[3]), pack_bf16(dg[4], dg[5]), pack_bf16(dg[6], dg[7]));
+      *reinterpret_cast<uint4*>(A.c1 + o) =
+          make_uint4(pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3]), pack_bf16(du[4], du[5]), pack_bf16(du[6], du[7]));
+      *reinterpret_cast<uint4*>(A.c2 + o) =
+          make_uint4(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]), pack_bf16(h[4], h[5]), pack_bf16(h[6], h[7]));
+    }
+  };
   if (SPLITK && split > 1) {
-    // ---- a part of a split tile: fp32 partial tile -> workspace, then whoever arrives last reduces
+    // ---- a part of a split tile: fp32 partial tile [row][256] -> workspace, then whoever arrives last reduces
     float* mine = A.partial + (size_t)part_slot * (TALL * TILE);
 #pragma unroll
     for (int b = 0; b < PB; b++) {
@@ -501,46 +555,59 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
         }
       __builtin_amdgcn_s_waitcnt(0xC07F);
       __builtin_amdgcn_wave_barrier();
+      constexpr int LPR = W / 4;          // lanes per row (4 fp32 per lane)
+      constexpr int RPI = 64 / LPR;       // rows per instruction
 #pragma unroll
-      for (int it = 0; it < 8; it++) {  // 4 rows x 16 lanes x 16 bytes per instruction
-        const int r = it * 4 + (lane >> 4);
-        const int q = (lane & 15) * 4;
-        if (wp + 32 * b + r < p_valid && q_base + q < q_valid)   // (the reduction reads only valid rows and columns)
+      for (int it = 0; it < 32 / RPI; it++) {
+        const int r = it * RPI + lane / LPR;
+        const int q = (lane % LPR) * 4;
+        if (wp + 32 * b + r < p_valid && q_base + q < q_valid) {  // (the reduction reads only valid rows and columns)
           *reinterpret_cast<float4*>(mine + (size_t)(wp + 32 * b + r) * TILE + q_base + q) =
               *reinterpret_cast<const float4*>(wlds + r * PITCH + q * 4);
+        }
       }
       __builtin_amdgcn_s_waitcnt(0xC07F);
       __builtin_amdgcn_wave_barrier();
     }
     // All parts of a tile carry the same blockIdx.x % 8 and so run on one XCD, whose L2 they share: a store that has
     // been acknowledged (vmcnt) is then visible to the other parts at the L2, and no cache has to be written back or
-    // invalidated; the reducing part reads the partial tiles at agent scope, i.e. past its own vector L1.  That placement is checked, not assumed: a part that finds itself on another XCD falls back to
-    // device-wide fences and says so in the upper half of the counter, which makes the reducing part fence as well.
+    // invalidated; the reducing part reads the partial tiles at agent scope, i.e. past its own vector L1.  That
+    // placement is checked, not assumed: a part that finds itself on another XCD falls back to device-wide fences and
+    // says so in the upper half of the counter, which makes the reducing part fence as well.
     __shared__ int arrived_before;
     const bool on_home_xcd = (__builtin_amdgcn_s_getreg((31 << 11) | 20) & 0xF) == (unsigned)(blockIdx.x % kNumXcd);
     if (on_home_xcd) __builtin_amdgcn_s_waitcnt(0x0F70);  // this thread's part of the partial tile has reached the L2
     else __threadfence();
     __syncthreads();   // ... and so has every other thread's, before the arrival is counted
-    if (tid == 0)
-      arrived_before = atomicAdd(A.counters + (part_slot / kCusPerXcd) * (kCusPerXcd / 2) + (part_slot % kCusPerXcd) / split,
-                                 on_home_xcd ? 1 : 0x10001);
+    int32_t* const arrivals = A.counters + (part_slot / kCusPerXcd) * (kCusPerXcd / 2) + (part_slot % kCusPerXcd) / split;
+    if (tid == 0) arrived_before = atomicAdd(arrivals, on_home_xcd ? 1 : 0x10001);
     __syncthreads();
     if ((arrived_before & 0xFFFF) != split - 1) return;
+    if (tid == 0) *arrivals = 0;   // every part has arrived: the counter is clear again for the next kernel that splits tiles
     if (!on_home_xcd || (arrived_before >> 16)) __threadfence();  // some part wrote through another XCD's L2
     const float* parts = A.partial + (size_t)(part_slot - part) * (TALL * TILE);
-    // the valid part of the tile only: p_valid rows of ceil(q_valid / 8) groups of 8 columns, spread over all threads
+    // the valid part of the tile only: p_valid rows of ceil(q_valid / 8) groups of 8 columns, spread over all threads;
+    // the parts are added in part order
     const int nqv = (q_valid + 7) >> 3;
     const int n_items = p_valid * nqv;
     for (int idx = tid; idx < n_items; idx += NTHREADS) {
       const int p = idx / nqv, q = (idx - p * nqv) * 8;
       float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int sp = 0; sp < split; sp++) {
-        const f32x4 x0 = load_agent_f4(parts + (size_t)sp * (TALL * TILE) + p * TILE + q);
-        const f32x4 x1 = load_agent_f4(parts + (size_t)sp * (TALL * TILE) + p * TILE + q + 4);
-        x[0] += x0.x; x[1] += x0.y; x[2] += x0.z; x[3] += x0.w; x[4] += x1.x; x[5] += x1.y; x[6] += x1.z; x[7] += x1.w;
+      const float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      const float* src = parts + p * TILE + q;
+      for (int sp = 0; sp < split; sp += 4) {   // four parts' 32 bytes in flight (parts past the last: the last again, not added)
+        f32x4 v[8];
+        load8_agent(v, src + (size_t)sp * (TALL * TILE), src + (size_t)min(sp + 1, split - 1) * (TALL * TILE),
+                    src + (size_t)min(sp + 2, split - 1) * (TALL * TILE), src + (size_t)min(sp + 3, split - 1) * (TALL * TILE));
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          if (sp + j < split) {
+            x[0] += v[2 * j].x; x[1] += v[2 * j].y; x[2] += v[2 * j].z; x[3] += v[2 * j].w;
+            x[4] += v[2 * j + 1].x; x[5] += v[2 * j + 1].y; x[6] += v[2 * j + 1].z; x[7] += v[2 * j + 1].w;
+          }
+        }
       }
-      *reinterpret_cast<uint4*>(A.c0 + (size_t)(p_row0 + p) * A.c_ld + q0_col + q) =
-          make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+      emit8((size_t)(p_row0 + p) * A.c_ld + q0_col + q, x, y);
     }
     return;
   }
@@ -601,43 +668,13 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
           const float4 x0 = *reinterpret_cast<const float4*>(wlds + r * PITCH + q * 4);
           const float4 x1 = *reinterpret_cast<const float4*>(wlds + r * PITCH + q * 4 + 16);
           const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-          if (EPI == EPI_BF16) {
-            *reinterpret_cast<uint4*>(A.c0 + o) =
-                make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
-          } else if (EPI == EPI_SWIGLU) {  // x = G; the second staged tensor is U
+          float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          if (EPI == EPI_SWIGLU) {  // the second staged tensor is U
             const float4 y0 = *reinterpret_cast<const float4*>(wlds + 8192 + r * PITCH + q * 4);
             const float4 y1 = *reinterpret_cast<const float4*>(wlds + 8192 + r * PITCH + q * 4 + 16);
-            const float u[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
-            float h[8];
-#pragma unroll
-            for (int i = 0; i < 8; i++) h[i] = x[i] * __builtin_amdgcn_rcpf(1.0f + __expf(-x[i])) * u[i];   // (rcp: 1 ulp, bf16 result)
-            *reinterpret_cast<uint4*>(A.c0 + o) =
-                make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
-            *reinterpret_cast<uint4*>(A.c1 + o) =
-                make_uint4(pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3]), pack_bf16(u[4], u[5]), pack_bf16(u[6], u[7]));
-            *reinterpret_cast<uint4*>(A.c2 + o) =
-                make_uint4(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]), pack_bf16(h[4], h[5]), pack_bf16(h[6], h[7]));
-          } else {  // EPI_DSWIGLU: x = dH; read saved G, U; write dG, dU, H
-            const uint4 gi = *reinterpret_cast<const uint4*>(A.g_in + o);
-            const uint4 ui = *reinterpret_cast<const uint4*>(A.u_in + o);
-            const float g[8] = {bf16lo(gi.x), bf16hi(gi.x), bf16lo(gi.y), bf16hi(gi.y), bf16lo(gi.z), bf16hi(gi.z), bf16lo(gi.w), bf16hi(gi.w)};
-            const float u[8] = {bf16lo(ui.x), bf16hi(ui.x), bf16lo(ui.y), bf16hi(ui.y), bf16lo(ui.z), bf16hi(ui.z), bf16lo(ui.w), bf16hi(ui.w)};
-            float dg[8], du[8], h[8];
-#pragma unroll
-            for (int i = 0; i < 8; i++) {
-              const float sg = __builtin_amdgcn_rcpf(1.0f + __expf(-g[i]));   // (rcp: 1 ulp, bf16 results)
-              const float sl = g[i] * sg;
-              h[i] = sl * u[i];
-              du[i] = x[i] * sl;
-              dg[i] = x[i] * u[i] * (sg * (1.0f + g[i] * (1.0f - sg)));
-            }
-            *reinterpret_cast<uint4*>(A.c0 + o) =
-                make_uint4(pack_bf16(dg[0], dg[1]), pack_bf16(dg[2], dg[3]), pack_bf16(dg[4], dg[5]), pack_bf16(dg[6], dg[7]));
-            *reinterpret_cast<uint4*>(A.c1 + o) =
-                make_uint4(pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3]), pack_bf16(du[4], du[5]), pack_bf16(du[6], du[7]));
-            *reinterpret_cast<uint4*>(A.c2 + o) =
-                make_uint4(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]), pack_bf16(h[4], h[5]), pack_bf16(h[6], h[7]));
+            y[0] = y0.x; y[1] = y0.y; y[2] = y0.z; y[3] = y0.w; y[4] = y1.x; y[5] = y1.y; y[6] = y1.z; y[7] = y1.w;
           }
+          emit8(o, x, y);
         }
       }
     }
@@ -703,7 +740,7 @@ template <int KIND, bool P_RC, bool Q_RC, int NQ, int NPASS, int EPI>
 static int launch_gemm(const char* label, const GemmArgs& A, long long max_blocks, hipStream_t st) {
   auto kern = grouped_gemm_kernel<KIND, P_RC, Q_RC, NQ, NPASS, EPI>;
   // bf16-output row-tile problems may cut the tiles of an XCD's last round into up to 32 parts in all
-  const long long per_xcd = (max_blocks + kNumXcd - 1) / kNumXcd + ((KIND == 0 && EPI == EPI_BF16) ? kCusPerXcd : 0);
+  const long long per_xcd = (max_blocks + kNumXcd - 1) / kNumXcd + ((KIND == 0 && NQ == 1) ? kCusPerXcd : 0);
   const long long grid = per_xcd * kNumXcd;
   if (max_blocks <= 0) return MOE_OK;
   MOE_LAUNCH(label, st, kern, dim3((unsigned)grid), dim3(NTHREADS), 0, st, A);

@@ -351,13 +351,22 @@ def test_grouped_ffn_fwd_bwd(moe, T, d, f, E, k, Es, dead):
         assert torch.all(gwu[e] == base)
 
 
-@pytest.mark.parametrize("d,f", [(128, 256), (256, 1088)])
-def test_grouped_ffn_every_tile_height(moe, d, f):
+HEIGHT_COUNTS = [1, 31, 33, 64, 65, 128, 129, 256, 257, 300, 320, 321, 0, 577, 512 + 65]
+FEW_COUNTS = [33, 300, 65, 0, 130]
+
+
+@pytest.mark.parametrize("d,f,counts", [(128, 256, HEIGHT_COUNTS), (256, 1088, HEIGHT_COUNTS), (3072, 256, HEIGHT_COUNTS),
+                                        (128, 3136, HEIGHT_COUNTS), (3072, 1536, FEW_COUNTS)])
+def test_grouped_ffn_every_tile_height(moe, d, f, counts):
     """Experts whose row counts hit every height class of a row tile and both sides of every class boundary: 1..64 rows
     (one 32-row block per wavefront), 65..128, 129..256, 257..320 (a full tile that carries up to 64 more rows), 321
     (a full tile plus a short one), an empty expert, and a multi-tile expert whose remainder rides on its last tile.
-    (f = 1088 = 4 * 256 + 64 also puts a 64-wide last column tile and a K long enough for the split tail on every class.)"""
-    counts = np.array([1, 31, 33, 64, 65, 128, 129, 256, 257, 300, 320, 321, 0, 577, 512 + 65], dtype=np.int64)
+    (f = 1088 = 4 * 256 + 64 also puts a 64-wide last column tile on every class.  The last two shapes make few tiles
+    with a contraction of 48 k-steps or more, which the kernels then cut along K: d = 3072 in dH, whose arriving part
+    applies the d(SwiGLU) epilogue to the summed parts, and f = 3136 = 49 * 64 in the down projection and in dX; the
+    last case, on a few experts, has both dH and dX cut their tiles in one backward call, one after the other on the
+    same arrival counters.)"""
+    counts = np.array(counts, dtype=np.int64)
     E, N = counts.size, int(counts.sum())
     offsets = np.zeros(E + 1, dtype=np.int32)
     offsets[1:] = np.cumsum(counts)
@@ -392,7 +401,8 @@ def test_grouped_ffn_every_tile_height(moe, d, f):
     assert_close(gwg.cpu().numpy(), dWg, qWg, what="dw_gate")
     assert_close(gwu.cpu().numpy(), dWu, qWu, what="dw_up")
     assert_close(gwd.cpu().numpy(), dWd, qWd, what="dw_down")
-    assert not gwg[12].any() and not gwd[12].any()          # the empty expert
+    empty = int(np.nonzero(counts == 0)[0][0])
+    assert not gwg[empty].any() and not gwd[empty].any()    # the empty expert
 
 
 # ---------------------------------------------------------------------------------------------------------
