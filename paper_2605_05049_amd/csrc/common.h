@@ -125,8 +125,8 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : M
 // Router backward pieces that live beside the router's forward kernel (router.hip) and are launched from the entry
 // point that also launches the grouped GEMM kernel (grouped_gemm.hip).
 void launch_router_prepare(hipStream_t st, const float* dlogits, const uint16_t* w_router, uint16_t* hi, uint16_t* lo, uint16_t* w_t,
-                           int32_t* offsets2, int32_t* part_order, uint32_t* zero_page, int T, int E, int Epad, int Ek, int d, int S,
-                           int part_rows);
+                           int32_t* offsets2, int32_t* part_order, int32_t* tile_queue, uint32_t* zero_page, int T, int E, int Epad, int Ek,
+                           int d, int S, int part_rows);
 void launch_router_bwd_dx(hipStream_t st, const uint16_t* dl_hi, const uint16_t* dl_lo, const uint16_t* w_t, uint16_t* dx, int T, int d,
                           int E, int Epad);
 void launch_router_dw_reduce(hipStream_t st, const float* partial, float* dw, int S, int E, int d, int ldp, int accumulate);

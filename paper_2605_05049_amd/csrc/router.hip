@@ -138,12 +138,14 @@ static void launch_router_fwd(hipStream_t st, dim3 grid, int neb, const uint16_t
 // padded), so that the expert index is the contiguous one for the dx kernel's fragments; writes the offset arrays of
 // the GEMM-path problems: {0, T} at [0..1], {0, E} at [4..5], and at [8 .. 8 + S] the S + 1 bounds of the S equal
 // parts of the token range that the dW_r contraction is cut into; and what the weight-gradient kernel reads of a
-// schedule: the order of its segments (the parts in turn: they are equally long but for the last) and the zero page.
+// schedule: the order of its segments (the parts in turn: they are equally long but for the last), the zero page and
+// its zeroed tile queue.
 __global__ __launch_bounds__(256) void router_prepare_kernel(const float* __restrict__ dlogits, const uint16_t* __restrict__ w_router,
                                                              uint16_t* __restrict__ hi, uint16_t* __restrict__ lo,
                                                              uint16_t* __restrict__ w_t, int32_t* __restrict__ offsets2,
-                                                             int32_t* __restrict__ part_order, uint32_t* __restrict__ zero_page,
-                                                             int T, int E, int Epad, int Ek, int d, int S, int part_rows) {
+                                                             int32_t* __restrict__ part_order, int32_t* __restrict__ tile_queue,
+                                                             uint32_t* __restrict__ zero_page, int T, int E, int Epad, int Ek, int d, int S,
+                                                             int part_rows) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i == 0) {
     offsets2[0] = 0; offsets2[1] = T;
@@ -152,6 +154,7 @@ __global__ __launch_bounds__(256) void router_prepare_kernel(const float* __rest
   if (i <= S) offsets2[8 + i] = (int)min((long long)T, i * part_rows);
   if (i < S) part_order[i] = (int)i;
   if (i < 64) zero_page[i] = 0u;
+  if (i < 8) tile_queue[i] = 0;
   if (w_t != nullptr && i < (long long)d * (Ek / 8)) {
     const int dcol = (int)(i % d), ec = (int)(i / d);
     uint32_t v[4];
@@ -333,11 +336,11 @@ __global__ __launch_bounds__(256) void router_dw_reduce_kernel(const float* __re
 }
 
 void launch_router_prepare(hipStream_t st, const float* dlogits, const uint16_t* w_router, uint16_t* hi, uint16_t* lo, uint16_t* w_t,
-                           int32_t* offsets2, int32_t* part_order, uint32_t* zero_page, int T, int E, int Epad, int Ek, int d, int S,
-                           int part_rows) {
+                           int32_t* offsets2, int32_t* part_order, int32_t* tile_queue, uint32_t* zero_page, int T, int E, int Epad, int Ek,
+                           int d, int S, int part_rows) {
   const long long n = max((long long)T * Epad, max((long long)d * (Ek / 8), 64LL));
   MOE_LAUNCH("router_prepare", st, router_prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dlogits, w_router, hi, lo, w_t,
-             offsets2, part_order, zero_page, T, E, Epad, Ek, d, S, part_rows);
+             offsets2, part_order, tile_queue, zero_page, T, E, Epad, Ek, d, S, part_rows);
 }
 
 void launch_router_bwd_dx(hipStream_t st, const uint16_t* dl_hi, const uint16_t* dl_lo, const uint16_t* w_t, uint16_t* dx, int T, int d,
