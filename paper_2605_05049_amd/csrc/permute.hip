@@ -88,7 +88,13 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ b
   const bool active = g < G;
   int sum = 0;
   if (active)
-    for (int b = b0; b < b1; b++) sum += block_hist[(size_t)b * Et + e];
+    for (int b = b0; b < b1; b += 8) {   // 8 loads in flight
+      int c[8];
+#pragma unroll
+      for (int j = 0; j < 8; j++) c[j] = (b + j < b1) ? block_hist[(size_t)(b + j) * Et + e] : 0;
+#pragma unroll
+      for (int j = 0; j < 8; j++) sum += c[j];
+    }
   if (active) part[g * Et + e] = sum;
   __syncthreads();
   if (tid < Et) {
@@ -102,15 +108,25 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ b
   } else {
     tot[tid] = 0;
   }
-  scan[tid] = (tid < Et) ? tot[tid] : 0;
+  // inclusive scan over the (at most 1024) experts: inside each wavefront with lane shuffles, then over the 16
+  // wavefront totals
+  __shared__ int32_t wave_total[kMaxExperts / kWave];
   __syncthreads();
-  // Hillis-Steele inclusive scan over the (at most 1024) experts
-  for (int o = 1; o < kMaxExperts; o <<= 1) {
-    int v = (tid >= o) ? scan[tid - o] : 0;
+  {
+    const int lane = tid % kWave, wv = tid / kWave;
+    int v = (tid < Et) ? tot[tid] : 0;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(v, o, kWave);
+      if (lane >= o) v += up;
+    }
+    if (lane == kWave - 1) wave_total[wv] = v;
     __syncthreads();
-    scan[tid] += v;
-    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wv; w++) before += wave_total[w];
+    scan[tid] = v + before;
   }
+  __syncthreads();
   if (tid < Et) {
     counts[tid] = tot[tid];
     offsets[tid] = scan[tid] - tot[tid];
@@ -118,10 +134,15 @@ __global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t* __restrict__ b
   }
   if (active) {
     int run = scan[e] - tot[e] + part[g * Et + e];
-    for (int b = b0; b < b1; b++) {
-      const int c = block_hist[(size_t)b * Et + e];
-      block_hist[(size_t)b * Et + e] = run;
-      run += c;
+    for (int b = b0; b < b1; b += 8) {   // 8 loads in flight
+      int c[8];
+#pragma unroll
+      for (int j = 0; j < 8; j++) c[j] = (b + j < b1) ? block_hist[(size_t)(b + j) * Et + e] : 0;
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        if (b + j < b1) block_hist[(size_t)(b + j) * Et + e] = run;
+        run += c[j];
+      }
     }
   }
 }
