@@ -165,4 +165,26 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 }
 __device__ __forceinline__ uint16_t f32_to_bf16(float v) { return (uint16_t)(pack_bf16(v, 0.f) & 0xffffu); }
 
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// One direct global->LDS load: 16 bytes per lane, lane L lands at lds_base + 16 L (lds_base is wave-uniform).
+// Written as inline assembly on purpose: the compiler does not track it, so it never makes the (transposing)
+// fragment reads of the OTHER stage wait for loads still in flight.  A kernel that uses them orders them itself: an
+// explicit s_waitcnt vmcnt(0) precedes the barrier that publishes a stage, and no compiler-tracked vector-memory
+// load is in flight while these are (the epilogue starts after the last such wait).  m0 receives the LDS base: the
+// backend reserves m0 (it is never allocated, and the compiler writes it only directly before an instruction of its
+// own that reads it; the kernels here have none: no LDS-direct or GDS access, no register-indexed moves, no messages).  Two
+// address forms: a 64-bit address per lane, or a scalar base plus a 32-bit byte offset per lane.
+__device__ __forceinline__ void direct_load16(const void* g, const char* lds_dst) {
+  const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)lds_dst);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(g) : "memory");
+}
+__device__ __forceinline__ void direct_load16(const void* sbase, unsigned voff, const char* lds_dst) {
+  const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)lds_dst);
+  const unsigned long long b = (unsigned long long)sbase;  // wave-uniform by construction; tell the compiler so
+  const unsigned long long sb = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                                (unsigned)__builtin_amdgcn_readfirstlane((int)b);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds), "v"(voff), "s"(sb) : "memory");
+}
+
 }  // namespace moe

@@ -108,8 +108,6 @@ struct TileOperand {
   int r_valid;              // valid r per half (<= 128 when split, <= 256 otherwise); beyond: clamped, never stored
 };
 
-typedef __attribute__((address_space(3))) void* lptr_t;
-
 // A 32 KB operand stage is filled by 32 direct-load instructions of 1 KB (instruction n fills LDS bytes [1024 n, +1024),
 // lane L the 16 bytes at +16 L); wavefront w issues instructions 4w..4w+3.  This returns the byte offset of lane L's 16
 // source bytes from the origin of the stage in global memory, i.e. from element (r = 0, k = first k of the step) of
@@ -135,26 +133,6 @@ __device__ __forceinline__ unsigned load_offset(const TileOperand& op, int n, in
     col = col < op.r_valid ? col : max(op.r_valid - 8, 0);  // (operands narrower than 8 are padded by their owner)
     return (unsigned)(((size_t)kr * op.ld + col) * 2);
   }
-}
-
-// One direct global->LDS load: 16 bytes per lane, lane L lands at lds_base + 16 L (lds_base is wave-uniform).
-// Written as inline assembly on purpose: the compiler does not track it, so it never makes the (transposing)
-// fragment reads of the OTHER stage wait for loads still in flight.  The kernel orders these loads itself: an
-// explicit s_waitcnt vmcnt(0) precedes the barrier that publishes a stage, and no compiler-tracked vector-memory
-// load is in flight while these are (the epilogue starts after the last such wait).  m0 receives the LDS base: the
-// backend reserves m0 (it is never allocated, and the compiler writes it only directly before an instruction of its
-// own that reads it; this kernel has none: no LDS-direct or GDS access, no register-indexed moves, no messages).  Two
-// address forms: a 64-bit address per lane, or a scalar base plus a 32-bit byte offset per lane.
-__device__ __forceinline__ void direct_load16(const void* g, const char* lds_dst) {
-  const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)lds_dst);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(g) : "memory");
-}
-__device__ __forceinline__ void direct_load16(const void* sbase, unsigned voff, const char* lds_dst) {
-  const unsigned lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)lds_dst);
-  const unsigned long long b = (unsigned long long)sbase;  // wave-uniform by construction; tell the compiler so
-  const unsigned long long sb = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
-                                (unsigned)__builtin_amdgcn_readfirstlane((int)b);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds), "v"(voff), "s"(sb) : "memory");
 }
 
 // Issues this wavefront's 4 direct loads of one operand stage for the 64 k-values starting at k0 (`delta`: element

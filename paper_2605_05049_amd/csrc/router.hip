@@ -8,7 +8,8 @@
 // and is re-read 8/TB times the bytes of x at E = 128), no LDS, no barrier in the loop.  The 8 wavefronts of a block
 // are the 8 parts of K of the SAME tokens; their partial sums meet in LDS at the end and are added in part order, so
 // the result never depends on timing and the whole call is a single launch.  TB is chosen from T so that the grid
-// has at least one block per CU.
+// has at least one block per CU.  (Many experts and many tokens take the second forward kernel below, which stages both
+// operands through LDS; the backward's kernels follow it.)
 //
 // MFMA 16x16x32 bf16: A = 16 experts x 32 k (lane l: expert l%16, k = 8 (l/16) .. +7), B = 16 tokens x 32 k (same
 // pattern), D[expert][token]: lane l holds token l%16 and experts 4 (l/16) .. +3, i.e. 4 consecutive logits of a row.
@@ -115,6 +116,98 @@ __global__ __launch_bounds__(kRouterWaves * kWave) void router_fwd_kernel(const 
       for (int p = 0; p < kRouterWaves; p++) sum += part_sum[p][j][idx];
       const int t = t0 + 16 * (q % TB) + (idx >> 4), e = e0 + 16 * (q / TB) + (idx & 15);
       if (t < T && e < E) logits[(size_t)t * E + e] = sum;
+    }
+  }
+}
+
+// The same map for many experts and many tokens (E > 32, T >= 8192).  There every block of the kernel above also
+// streams its expert tile's whole W_r (1 MB at E = 128) for 64 tokens, twice the bytes of its x rows, and the MFMA
+// operand layout makes every load fetch 64 bytes of 16 different lines.  Here both operands go through LDS instead:
+// a block of 8 wavefronts owns 64 tokens x 32 NEBH experts and walks all of K in steps of 64 (whole 128-byte lines,
+// direct global->LDS loads, one instruction = 8 rows, chunks XOR-swizzled with the row so that the fragment reads are
+// conflict-free), through a ring of four stages of (64 + 32 NEBH) x 128 bytes, three steps ahead; wavefront w
+// multiplies token block w % 4 with expert half w / 4.  Every wavefront issues three loads per stage (one of x, two of
+// W_r), so "all but the two youngest stages" is vmcnt(6).  No K split: each logit is one wavefront's sum.
+template <int NEBH>
+__global__ __launch_bounds__(kRouterWaves * kWave) void router_fwd_wide_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router,
+                                                                               float* __restrict__ logits, int T, int E, int d) {
+  constexpr int XROWS = 64, WROWS = 32 * NEBH;
+  constexpr int STAGE = (XROWS + WROWS) * 128;   // bytes
+  __shared__ __attribute__((aligned(1024))) char ring[4][STAGE];
+  const int lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 15, kg = lane >> 4;
+  const int t0 = blockIdx.x * XROWS, e0 = blockIdx.y * WROWS;
+  const int tb = wave & 3, eh = wave >> 2;
+  const int n_steps = d / 64;
+
+  // direct loads: instruction i of an operand = rows 8 i .. 8 i + 7, lane L = row 8 i + L / 8, the 16-byte chunk
+  // (L % 8) ^ ((row >> 1) & 7) of the row's 128 bytes of this step; rows past the end are clamped (never stored)
+  auto src_off = [&](int row_in_tile, int limit_rows) -> unsigned {
+    const int r = min(row_in_tile, limit_rows - 1);
+    const int c = (lane & 7) ^ ((row_in_tile >> 1) & 7);
+    return (unsigned)(((size_t)r * d + c * 8) * 2);
+  };
+  const uint16_t* xbase = x + (size_t)t0 * d;
+  const uint16_t* wbase = w_router + (size_t)e0 * d;
+  const unsigned xo = src_off(8 * wave + (lane >> 3), T - t0);
+  unsigned wo[NEBH / 2 > 0 ? NEBH / 2 : 1];   // W_r instructions of this wavefront: WROWS / 8 / 8 = NEBH / 2
+#pragma unroll
+  for (int i = 0; i < NEBH / 2; i++) wo[i] = src_off(8 * (wave * (NEBH / 2) + i) + (lane >> 3), E - e0);
+  constexpr int LOADS = 1 + NEBH / 2;   // per wavefront and stage
+  static_assert(LOADS == 3 || LOADS == 2, "the wait counts below are written for NEBH = 4 or 2");
+  auto issue = [&](int step, char* stage) __attribute__((always_inline)) {
+    direct_load16(xbase + (size_t)step * 64, xo, stage + wave * 1024);
+#pragma unroll
+    for (int i = 0; i < NEBH / 2; i++) direct_load16(wbase + (size_t)step * 64, wo[i], stage + XROWS * 128 + (wave * (NEBH / 2) + i) * 1024);
+  };
+  // fragment of 16 rows x 32 k: lane (n, kg) reads chunk 4 g + kg of row r0 + n
+  auto frag = [&](const char* rows, int r0, int g) __attribute__((always_inline)) -> r_bf16x8 {
+    const int r = r0 + n;
+    return *reinterpret_cast<const r_bf16x8*>(rows + r * 128 + (((4 * g + kg) ^ ((r >> 1) & 7)) << 4));
+  };
+
+  r_f32x4 acc[NEBH];
+#pragma unroll
+  for (int m = 0; m < NEBH; m++) acc[m] = r_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s0 = 0; s0 < 3; s0++)
+    if (s0 < n_steps) issue(s0, ring[s0]);
+  for (int step = 0; step < n_steps; step++) {
+    // loads of steps step + 1 and step + 2 may still be in flight
+    const int younger = min(2, n_steps - 1 - step);
+    if (younger == 2) {
+      if (LOADS == 3) __builtin_amdgcn_s_waitcnt(0x0F76); else __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(6) / vmcnt(4)
+    } else if (younger == 1) {
+      if (LOADS == 3) __builtin_amdgcn_s_waitcnt(0x0F73); else __builtin_amdgcn_s_waitcnt(0x0F72);   // vmcnt(3) / vmcnt(2)
+    } else {
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
+    __syncthreads();   // this step's stage has landed for everyone; everyone is done with the stage of step - 1
+    if (step + 3 < n_steps) issue(step + 3, ring[(step + 3) & 3]);
+    const char* xs = ring[step & 3];
+    const char* ws = xs + XROWS * 128;
+#pragma unroll
+    for (int g = 0; g < 2; g++) {
+      const r_bf16x8 xf = frag(xs, 16 * tb, g);
+#pragma unroll
+      for (int m = 0; m < NEBH; m++) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(ws, 16 * (eh * NEBH + m), g), xf, acc[m], 0, 0, 0);
+    }
+  }
+  // acc[m][i] = logit (token t0 + 16 tb + n, expert e0 + 16 (eh NEBH + m) + 4 kg + i)
+  const int t = t0 + 16 * tb + n;
+  if (t < T) {
+#pragma unroll
+    for (int m = 0; m < NEBH; m++) {
+      const int e = e0 + 16 * (eh * NEBH + m) + 4 * kg;
+      float* dst = logits + (size_t)t * E + e;
+      if ((E & 3) == 0 && e + 4 <= E) {
+        *reinterpret_cast<r_f32x4*>(dst) = acc[m];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+          if (e + i < E) dst[i] = acc[m][i];
+      }
     }
   }
 }
@@ -376,6 +469,17 @@ extern "C" int moe_router_fwd(const moe_shape* shape, const uint16_t* x, const u
   MOE_REQUIRE_ALIGNED(x); MOE_REQUIRE_ALIGNED(w_router); MOE_REQUIRE_ALIGNED(logits);
   if (D.T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
+  if (D.E > 32 && D.T >= 8192) {   // many experts, many tokens: both operands through LDS
+    const dim3 block(kRouterWaves * kWave);
+    if (D.E <= 64) {
+      MOE_LAUNCH("router_fwd", st, (router_fwd_wide_kernel<2>), dim3((unsigned)((D.T + 63) / 64), (unsigned)((D.E + 63) / 64)), block, 0, st, x, w_router,
+                 logits, (int)D.T, (int)D.E, (int)D.d);
+    } else {
+      MOE_LAUNCH("router_fwd", st, (router_fwd_wide_kernel<4>), dim3((unsigned)((D.T + 63) / 64), (unsigned)((D.E + 127) / 128)), block, 0, st, x,
+                 w_router, logits, (int)D.T, (int)D.E, (int)D.d);
+    }
+    return launch_status();
+  }
   const unsigned e_tiles = (unsigned)((D.E + kRouterExpertTile - 1) / kRouterExpertTile);
   // tokens per block: 64 when that still gives every CU a block, else 32 or 16
   const int tb = (D.T >= 64 * 256) ? 4 : (D.T >= 32 * 256 ? 2 : 1);

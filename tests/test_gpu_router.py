@@ -35,6 +35,9 @@ ROUTER_SHAPES = [
     # every expert-group count of the skinny dx kernel (32, 64, 128 padded experts) with ragged E, more columns than one
     # block's 1024, fewer tokens than one stage of 64
     (500, 320, 96), (130, 1280, 33), (40, 2112, 32),
+    # the forward kernel for many experts and many tokens (both operands through LDS): 64- and 128-expert tiles, ragged
+    # E (also not a multiple of 4), a ragged token tail, two expert tiles
+    (8192, 256, 60), (8200, 128, 99), (8192, 192, 160),
     # the router of the two workloads bench.py times it on, at full size
     (4096, 4096, 8), (16384, 4096, 128),
 ]
