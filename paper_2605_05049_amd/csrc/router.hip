@@ -260,13 +260,26 @@ __global__ __launch_bounds__(256) void router_prepare_kernel(const float* __rest
     }
     *reinterpret_cast<uint4*>(w_t + (size_t)dcol * Ek + 8 * ec) = make_uint4(v[0], v[1], v[2], v[3]);
   }
-  if (i >= (long long)T * Epad) return;
-  const int t = (int)(i / Epad), e = (int)(i % Epad);
-  const float v = e < E ? dlogits[(size_t)t * E + e] : 0.f;
-  const uint32_t h2 = pack_bf16(v, 0.f) & 0xFFFFu;
-  const float hf = bf16lo(h2);
-  hi[i] = (uint16_t)h2;
-  lo[i] = (uint16_t)(pack_bf16(v - hf, 0.f) & 0xFFFFu);
+  // 8 consecutive experts of a token per thread (Epad is a multiple of 64): 16 bytes of each of the two copies
+  if (i >= (long long)T * (Epad / 8)) return;
+  const int t = (int)(i / (Epad / 8)), e0 = (int)(i % (Epad / 8)) * 8;
+  float v[8];
+  const float* src = dlogits + (size_t)t * E + e0;
+  if ((E & 3) == 0 && e0 + 8 <= E) {
+    const r_f32x4 a = *reinterpret_cast<const r_f32x4*>(src), b = *reinterpret_cast<const r_f32x4*>(src + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; j++) v[j] = (e0 + j < E) ? src[j] : 0.f;
+  }
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    h[j] = pack_bf16(v[2 * j], v[2 * j + 1]);
+    l[j] = pack_bf16(v[2 * j] - bf16lo(h[j]), v[2 * j + 1] - bf16hi(h[j]));
+  }
+  *reinterpret_cast<uint4*>(hi + (size_t)t * Epad + e0) = make_uint4(h[0], h[1], h[2], h[3]);
+  *reinterpret_cast<uint4*>(lo + (size_t)t * Epad + e0) = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
 // dx_router[t, c] = sum_e dlogits[t, e] W_r[e, c] for E <= 128: T x d x E with E small, so its time is the time to
@@ -431,7 +444,7 @@ __global__ __launch_bounds__(256) void router_dw_reduce_kernel(const float* __re
 void launch_router_prepare(hipStream_t st, const float* dlogits, const uint16_t* w_router, uint16_t* hi, uint16_t* lo, uint16_t* w_t,
                            int32_t* offsets2, int32_t* part_order, int32_t* tile_queue, uint32_t* zero_page, int T, int E, int Epad, int Ek,
                            int d, int S, int part_rows) {
-  const long long n = max((long long)T * Epad, max((long long)d * (Ek / 8), 64LL));
+  const long long n = max((long long)T * (Epad / 8), max((long long)d * (Ek / 8), 64LL));
   MOE_LAUNCH("router_prepare", st, router_prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dlogits, w_router, hi, lo, w_t,
              offsets2, part_order, tile_queue, zero_page, T, E, Epad, Ek, d, S, part_rows);
 }
