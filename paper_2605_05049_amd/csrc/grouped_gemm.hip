@@ -50,6 +50,7 @@ constexpr int NTHREADS = 512;
 constexpr int TALL = TILE + 64;                 // rows of a tall tile: an expert's last full row tile plus up to 64 rows
 constexpr int OPERAND_BYTES = TILE * BK * 2;    // 32 KB per 256-row operand per stage
 constexpr int Q_STAGE_OFFSET = TALL * BK * 2;   // the Q operand follows the (up to 320-row, 40 KB) P operand
+constexpr int P_AREA_BYTES = Q_STAGE_OFFSET;    // a stage's P operand
 constexpr int STAGE_BYTES = Q_STAGE_OFFSET + OPERAND_BYTES;  // P + Q = 72 KB
                                                 // two stages = 144 KB of the 160 KB of LDS
 constexpr int kNumXcd = 8;
@@ -65,6 +66,21 @@ constexpr int kCusPerXcd = 32;
 #endif
 #ifndef MOE_WGRAD_PERSISTENT
 #define MOE_WGRAD_PERSISTENT 1
+#endif
+// How far ahead of their MFMAs a k-step reads its fragments (0: each group of 16 k reads its own; 1: half a group
+// ahead; 2: rolling, see the k-step): for row tiles of up to 256 rows, for tall row tiles, for the tall row tiles of the
+// SwiGLU forward, and for the weight gradients (whose transposing reads gained nothing from 2).
+#ifndef MOE_FRAG_PIPELINE_ROW
+#define MOE_FRAG_PIPELINE_ROW 2
+#endif
+#ifndef MOE_FRAG_PIPELINE_TALL
+#define MOE_FRAG_PIPELINE_TALL 2
+#endif
+#ifndef MOE_FRAG_PIPELINE_TALL_SWIGLU
+#define MOE_FRAG_PIPELINE_TALL_SWIGLU 0
+#endif
+#ifndef MOE_FRAG_PIPELINE_WGRAD
+#define MOE_FRAG_PIPELINE_WGRAD 1
 #endif
 #ifndef MOE_EARLY_ISSUE_AT
 #define MOE_EARLY_ISSUE_AT 32   // k offset inside a step at which wavefronts 0..3 request their share of the next stage
@@ -200,6 +216,44 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int r0, int kk, in
   }
 }
 
+// The same fragment addressed in three parts: `off` = the lane's byte offset inside an operand area for kk = 0
+// (frag_offset), kk, and `area` = a wave-uniform constant (the LDS address of the operand area, plus 4096 bytes for every
+// 32 rows further down a K-contiguous operand, whose swizzle has a period of 16 rows).  kk flips two address bits
+// (K-contiguous: the 16-byte chunk index is XORed with the row's swizzle, and kk / 8 occupies bits of it that the
+// lane's own part leaves clear) or adds 512 bytes per k-row pair (R-contiguous).  Written this way the loop-invariant
+// part, off ^ 2 kk or off, is one register per operand and kk (K-contiguous) or per fragment (R-contiguous), and the
+// rest goes into the read instruction's 16-bit offset field: 8 to 12 address registers over the K loop where one
+// address per fragment, stage and kk took 48.
+template <bool RC>
+__device__ __forceinline__ unsigned frag_offset(int r0, int lane) {
+  if (!RC) {
+    const int r = r0 + (lane & 31);
+    return (unsigned)(r * 128 + (((lane >> 5) ^ ((r >> 1) & 7)) << 4));
+  } else {
+    const int p = lane & 15;
+    const int k = 8 * (lane >> 5) + (p >> 2);
+    const int relem = r0 + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
+    const int c = relem >> 3;
+    return (unsigned)(((((k >> 2) << 1) + (c >> 4)) << 10) + ((k & 3) << 8) + (((c & 15) ^ ((k & 3) << 2)) << 4) + ((relem & 7) << 1));
+  }
+}
+template <bool RC>
+__device__ __forceinline__ bf16x8 read_frag_at(unsigned off, int kk, unsigned area) {
+  if (!RC) {
+    typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+    return *reinterpret_cast<const lds_bf16x8*>((size_t)((off ^ (unsigned)(kk << 1)) + area));
+  } else {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const unsigned a = off + (unsigned)(kk * 512) + area;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(size_t)a);
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(size_t)(a + 2048u));
+    union { struct { s16x4 lo, hi; } s; bf16x8 v; } u;
+    u.s.lo = lo;
+    u.s.hi = hi;
+    return u.v;
+  }
+}
+
 // Row tiles of an expert with n rows.  Without tall tiles: ceil(n / 256).  With them, a remainder of at most 64 rows
 // does not get a tile of its own (which would stream the expert's whole weight panel once more for a handful of rows)
 // but rides on the last full tile, which then has up to 320 rows: max(1, ceil((n - 64) / 256)).
@@ -212,10 +266,10 @@ __host__ __device__ __forceinline__ int row_tiles_of(int n, int tall) {
 // NQ = 2: the q tile is two 128-wide halves from q0 and q1 (acc[0] = q0 result, acc[1] = q1 result at the same q).
 template <int KIND, bool P_RC, bool Q_RC, int NQ, int NPASS, int EPI>
 __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A) {
-  // Two stages as two distinct arrays: the compiler can then tell that a direct load into one stage does not
-  // alias the fragment reads of the other, and does not make those reads wait for the load.
-  __shared__ __attribute__((aligned(1024))) char stage0[STAGE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char stage1[STAGE_BYTES];
+  // Two stages of P (up to 320 rows) | Q each.
+  __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE_BYTES];
+  auto p_area = [&](int s) __attribute__((always_inline)) { return lds + s * STAGE_BYTES; };
+  auto q_area = [&](int s) __attribute__((always_inline)) { return lds + s * STAGE_BYTES + P_AREA_BYTES; };
   constexpr int TQ = TILE / NQ;  // q extent per output tensor
 
   const int tid = threadIdx.x;
@@ -276,9 +330,25 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     const int e_lo = A.offsets[expert], e_hi = A.offsets[expert + 1];
     const int e_tiles = row_tiles_of(e_hi - e_lo, A.sched[1]);
     const int first = A.sched[64 + A.max_tiles + u];  // index of the expert's first row tile
-    const long long local = lid - (long long)first * A.n_q_tiles;
-    const int qt = (int)(local / e_tiles);
-    const int mt = (int)(local % e_tiles);
+    // Order inside an expert: column tile after column tile, each with all its row tiles (32 consecutive tiles, which
+    // an XCD runs together, are then about 4 row tiles x 8 column tiles: 4 + 8 panels), a tall last row tile first.
+    // Blocks are handed to CUs in order as CUs become free, so a tile that takes longer should come early in its
+    // group of 32: an expert of at most 4 row tiles, whose 8 column tiles fill a group, is therefore walked row
+    // tile after row tile inside each band of 8 column tiles (the same 32 tiles, the 8 tall ones first: the CUs that
+    // ran the previous group's tall tiles then get ordinary ones).
+    const int local = (int)(lid - (long long)first * A.n_q_tiles);
+    int qt, m;
+    if (e_tiles <= 4) {
+      const int band = local / (e_tiles * 8), in_band = local % (e_tiles * 8);
+      const int band_q = min(8, A.n_q_tiles - band * 8);   // column tiles of this band
+      qt = band * 8 + in_band % band_q;
+      m = in_band / band_q;
+    } else {
+      qt = local / e_tiles;
+      m = local % e_tiles;
+    }
+    const bool tall_last = (e_hi - e_lo) - (e_tiles - 1) * TILE > TILE;
+    const int mt = tall_last ? (m == 0 ? e_tiles - 1 : m - 1) : m;
     p_row0 = e_lo + mt * TILE;
     p_valid = (mt == e_tiles - 1) ? e_hi - p_row0 : TILE;   // (the last tile may be a tall one: up to 320 rows)
     p_tile_idx = mt;
@@ -358,17 +428,17 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   const int nk_pass = (k_len + BK - 1) / BK;  // k-steps per K pass
   const int nk = nk_pass * NPASS;             // k-steps of the whole contraction
   // this wavefront's 8 direct loads of step j of the contraction
-  auto issue_as = [&](auto narrow_p, int j, char* stage) __attribute__((always_inline)) {
+  auto issue_as = [&](auto narrow_p, int j, char* p_dst, char* q_dst) __attribute__((always_inline)) {
     const bool second = (NPASS == 2) && j >= nk_pass;
     const int k0 = (second ? j - nk_pass : j) * BK;
-    issue_tile<P_RC, false, decltype(narrow_p)::value>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage, wave, lane);
-    issue_tile<Q_RC, NQ == 2>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, stage + Q_STAGE_OFFSET, iwq, lane);
+    issue_tile<P_RC, false, decltype(narrow_p)::value>(pvo, P, second ? p_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, p_dst, wave, lane);
+    issue_tile<Q_RC, NQ == 2>(qvo, Q, second ? q_pass_delta : (ptrdiff_t)0, k0, k_len, A.zero_page, q_dst, iwq, lane);
   };
   // the k-steps this block multiplies: all of them, or its part of a split tile
   const int kt_per = (nk + split - 1) / split;
   const int kt_begin = part * kt_per, kt_end = min(nk, kt_begin + kt_per);
   // (the first stage is requested before anything else is set up; rows a short tile does not have are clamped here)
-  if (kt_begin < kt_end) issue_as(std::false_type{}, kt_begin, stage0);
+  if (kt_begin < kt_end) issue_as(std::false_type{}, kt_begin, p_area(0), q_area(0));
   // Height class of the tile: each of the two wavefronts along p multiplies PB blocks of 32 rows (4, 2 or 1), so a
   // ragged last row tile of an expert issues MFMAs and row loads for its class (256, 128 or 64 rows) only.
   auto run = [&](auto pb_c) __attribute__((always_inline)) {
@@ -376,18 +446,18 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   // (a short tile leaves out the loads of the rows it does not have)
   // a tall tile's rows 256.. are one more instruction per wavefront (instruction 32 + wave: rows 256 + 8 wave .. +7)
   const unsigned pvo_tall = (PB == 5) ? load_offset<P_RC, false>(P, 32 + wave, lane) : 0u;
-  auto issue_tall = [&](int j, char* stage) __attribute__((always_inline)) {
+  auto issue_tall = [&](int j, char* p_dst) __attribute__((always_inline)) {
     if (PB == 5 && (32 + wave) * 8 < p_valid) {
       const bool second = (NPASS == 2) && j >= nk_pass;
       const int k0 = (second ? j - nk_pass : j) * BK;
-      direct_load16(P.base0 + (second ? p_pass_delta : (ptrdiff_t)0) + k0, pvo_tall, stage + (32 + wave) * 1024);
+      direct_load16(P.base0 + (second ? p_pass_delta : (ptrdiff_t)0) + k0, pvo_tall, p_dst + (32 + wave) * 1024);
     }
   };
-  auto issue = [&](int j, char* stage) __attribute__((always_inline)) {
-    issue_as(std::integral_constant<bool, (PB < 4)>{}, j, stage);
-    issue_tall(j, stage);
+  auto issue = [&](int j, int s) __attribute__((always_inline)) {
+    issue_as(std::integral_constant<bool, (PB < 4)>{}, j, p_area(s), q_area(s));
+    issue_tall(j, p_area(s));
   };
-  if (kt_begin < kt_end) issue_tall(kt_begin, stage0);   // (the rest of the first stage was requested above)
+  if (kt_begin < kt_end) issue_tall(kt_begin, p_area(0));   // (the rest of the first stage was requested above)
   const int wp = (wave & 1) * (PB * 32);  // p origin of this wavefront
   f32x16 acc[2][PB];  // [q sub-tile a][p sub-tile b]
 #pragma unroll
@@ -400,36 +470,119 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   // One k-step: wait for stage `cur`, multiply it, and meanwhile fill `nxt` with step kt+1.  The two wavefronts of a
   // SIMD request their share of the next stage at different times of the step (one before its MFMAs, the other
   // between its two halves of them), so that while one is held up issuing loads the other keeps the matrix pipe busy.
-  auto k_step = [&](const char* cur, char* nxt, int kt) {
+  // (next to a tall tile's 160 accumulator registers the SwiGLU forward, with its two q tensors, has no room for
+  // fragments in flight; a register spilled inside the K loop is ruinous here: its reload waits on the counter that
+  // the direct loads share)
+  constexpr int FRAG_PIPELINE = (PB == 5) ? (EPI == EPI_SWIGLU ? MOE_FRAG_PIPELINE_TALL_SWIGLU : MOE_FRAG_PIPELINE_TALL)
+                                          : (KIND == 0) ? MOE_FRAG_PIPELINE_ROW : MOE_FRAG_PIPELINE_WGRAD;
+  // Per-lane LDS offsets of this wavefront's fragments (at kk = 0) from the start of a stage.
+  unsigned p_off[PB], q_off[2];
+#pragma unroll
+  for (int b = 0; b < PB; b++) p_off[b] = frag_offset<P_RC>(wp + 32 * b, lane);
+  q_off[0] = frag_offset<Q_RC>(qr0, lane);
+  q_off[1] = frag_offset<Q_RC>(qr1, lane);
+  auto k_step = [&](int cur, int nxt, int kt) {
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this thread's loads of step kt have landed in LDS
     __syncthreads();                     // ... and everyone's; everyone is also done reading the other stage
     if (late && kt + 1 < kt_end) issue(kt + 1, nxt);
-    const char* p_lds = cur;
-    const char* q_lds = cur + Q_STAGE_OFFSET;
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
+    const unsigned p_base = (unsigned)(size_t)(lptr_t)p_area(cur), q_base = (unsigned)(size_t)(lptr_t)q_area(cur);
+    // (K-contiguous operand: 32 rows further is 4096 bytes further with the same swizzle, so all fragments of the
+    // operand share the address register of the first and differ in the instruction's offset field)
+    auto rp = [&](int b, int kk) __attribute__((always_inline)) {
+      return P_RC ? read_frag_at<P_RC>(p_off[b], kk, p_base) : read_frag_at<P_RC>(p_off[0], kk, p_base + 4096u * b);
+    };
+    auto rq = [&](int a, int kk) __attribute__((always_inline)) {
+      return Q_RC ? read_frag_at<Q_RC>(q_off[a], kk, q_base) : read_frag_at<Q_RC>(q_off[0], kk, q_base + 128u * (NQ == 2 ? 128 : 32) * a);
+    };
+    auto early_issue = [&](int kk) __attribute__((always_inline)) {
       if (kk == MOE_EARLY_ISSUE_AT) {
         __builtin_amdgcn_sched_barrier(0);
         if (!late && kt + 1 < kt_end) issue(kt + 1, nxt);
         __builtin_amdgcn_sched_barrier(0);
       }
-      bf16x8 pf[PB], qf[2];
-      qf[0] = read_frag<Q_RC>(q_lds, qr0, kk, lane);
-      qf[1] = read_frag<Q_RC>(q_lds, qr1, kk, lane);
+    };
+    if constexpr (FRAG_PIPELINE == 0) {
 #pragma unroll
-      for (int b = 0; b < PB; b++) pf[b] = read_frag<P_RC>(p_lds, wp + 32 * b, kk, lane);
+      for (int kk = 0; kk < BK; kk += 16) {
+        early_issue(kk);
+        bf16x8 pf[PB], qf[2];
+        qf[0] = rq(0, kk);
+        qf[1] = rq(1, kk);
 #pragma unroll
-      for (int b = 0; b < PB; b++)
+        for (int b = 0; b < PB; b++) pf[b] = rp(b, kk);
 #pragma unroll
-        for (int a = 0; a < 2; a++)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[a], pf[b], acc[a][b], 0, 0, 0);
+        for (int b = 0; b < PB; b++)
+#pragma unroll
+          for (int a = 0; a < 2; a++)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[a], pf[b], acc[a][b], 0, 0, 0);
+      }
+    } else if constexpr (FRAG_PIPELINE == 1) {
+      // The fragments of a group of 16 k are read half a group ahead of the MFMAs that use them: the p blocks of a
+      // group's second half while its first half multiplies, the q fragments (two sets) and the first p blocks of
+      // the next group while the second half does.
+      constexpr int HA = (PB + 1) / 2;   // p blocks of the first half
+      bf16x8 pf[PB], qf[2][2];
+      auto read_half_a = [&](int kk, bf16x8 (&q)[2]) __attribute__((always_inline)) {
+        q[0] = rq(0, kk);
+        q[1] = rq(1, kk);
+#pragma unroll
+        for (int b = 0; b < HA; b++) pf[b] = rp(b, kk);
+      };
+      read_half_a(0, qf[0]);
+#pragma unroll
+      for (int g = 0; g < BK / 16; g++) {
+        const int kk = 16 * g;
+        early_issue(kk);
+#pragma unroll
+        for (int b = HA; b < PB; b++) pf[b] = rp(b, kk);
+#pragma unroll
+        for (int b = 0; b < HA; b++)
+#pragma unroll
+          for (int a = 0; a < 2; a++)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[g & 1][a], pf[b], acc[a][b], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (g + 1 < BK / 16) read_half_a(kk + 16, qf[(g + 1) & 1]);
+#pragma unroll
+        for (int b = HA; b < PB; b++)
+#pragma unroll
+          for (int a = 0; a < 2; a++)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[g & 1][a], pf[b], acc[a][b], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+      // Rolling fragments: a p fragment is read again, for the next group of 16 k, right after the two MFMAs that use
+      // it; the two q fragments, which every MFMA of a group uses, alternate between two sets.  A wavefront that is
+      // alone on its SIMD's matrix pipe (its partner is held up issuing loads) then does not stall on the LDS latency
+      // between groups, and the LDS reads are spread evenly between the MFMAs.
+      bf16x8 pf[PB], qf[2][2];
+      qf[0][0] = rq(0, 0);
+      qf[0][1] = rq(1, 0);
+#pragma unroll
+      for (int b = 0; b < PB; b++) pf[b] = rp(b, 0);
+#pragma unroll
+      for (int g = 0; g < BK / 16; g++) {
+        const int kk = 16 * g;
+        const bool more = g + 1 < BK / 16;
+        early_issue(kk);
+#pragma unroll
+        for (int b = 0; b < PB; b++) {
+          acc[0][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[g & 1][0], pf[b], acc[0][b], 0, 0, 0);
+          acc[1][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[g & 1][1], pf[b], acc[1][b], 0, 0, 0);
+          if (more) {
+            pf[b] = rp(b, kk + 16);
+            if (b == 0) qf[(g + 1) & 1][0] = rq(0, kk + 16);
+            if (b == (PB > 2 ? 1 : 0)) qf[(g + 1) & 1][1] = rq(1, kk + 16);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
     }
   };
   // Tiles of at most 64 rows (PB == 1) multiply little per step and are bound by the latency of their loads, and
   // their P operand needs 8 KB of a stage's 40: they run a ring of three slots, two steps ahead instead of one.
-  //   slot 0: P at stage0, Q at stage0 + 40 KB (the layout of the first stage requested above)
-  //   slot 1: P at stage1, Q at stage1 + 40 KB
-  //   slot 2: P at stage1 + 8 KB, Q at stage0 + 8 KB (rows 64.. of the other slots' P areas, which these tiles never read)
+  //   slot 0: the first stage's areas (the first stage was requested above)
+  //   slot 1: the second stage's areas
+  //   slot 2: P at 8 KB into the second P area, Q at 8 KB into the first (rows 64.. of P areas, which these tiles never read)
   // Every wavefront issues one P instruction (rows 8 w .. 8 w + 7, clamped onto the tile's last row) and its four Q
   // instructions per step: 5 loads, the same for all, so that "all but the youngest step" is vmcnt(5).
   if constexpr (PB == 1) {
@@ -458,8 +611,8 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
         acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q1f, p0f, acc[1][0], 0, 0, 0);
       }
     };
-    char* const rp[3] = {stage0, stage1, stage1 + 8192};
-    char* const rq[3] = {stage0 + Q_STAGE_OFFSET, stage1 + Q_STAGE_OFFSET, stage0 + 8192};
+    char* const rp[3] = {p_area(0), p_area(1), p_area(1) + 8192};
+    char* const rq[3] = {q_area(0), q_area(1), p_area(0) + 8192};
     if (kt_begin + 1 < kt_end) issue1(kt_begin + 1, rp[1], rq[1]);
     for (int kt = kt_begin; kt < kt_end; kt += 3) {
       ring_step(rp[0], rq[0], rp[2], rq[2], kt);
@@ -468,8 +621,8 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     }
   } else {
     for (int kt = kt_begin; kt < kt_end; kt += 2) {
-      k_step(stage0, stage1, kt);
-      if (kt + 1 < kt_end) k_step(stage1, stage0, kt + 1);
+      k_step(0, 1, kt);
+      if (kt + 1 < kt_end) k_step(1, 0, kt + 1);
     }
   }
 
@@ -482,7 +635,7 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   constexpr int W = (NQ == 2) ? 32 : 64;       // q extent this wavefront owns per output tensor
   constexpr int PITCH = W * 4 + 16;            // bytes per staged fp32 row; the +16 keeps 16-byte accesses conflict-free
   __syncthreads();                             // every wavefront has finished reading the stages
-  char* wlds = ((wave < 4) ? stage0 : stage1) + (wave & 3) * 16384;
+  char* wlds = lds + wave * 16384;
   const int q_base = wq * W;                   // first q of this wavefront inside the output's tile
   // 8 consecutive outputs of a row: x (and, for the SwiGLU forward, the matching values y of the second tensor) ->
   // the kernel's bf16 outputs at element offset o
@@ -758,6 +911,12 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_persistent_kernel(const GemmAr
   char* const wlds = stage1 + wave * (STAGE_BYTES / 8);   // this wavefront's 9 KB of stage 1: NQ tensors of 32 x PITCH bytes
   const int q_base = wq * W;
 
+  unsigned p_off[PB], q_off[2];   // per-lane LDS offsets of this wavefront's fragments inside an operand area (kk = 0)
+#pragma unroll
+  for (int b = 0; b < PB; b++) p_off[b] = frag_offset<true>(wp + 32 * b, lane);
+  q_off[0] = frag_offset<true>(qr0, lane);
+  q_off[1] = frag_offset<true>(qr1, lane);
+
   WgradTile cur = decode(blockIdx.x / kNumXcd);   // the first tile of a block is its own index in its XCD
   bool first_stage_requested = false;
   while (cur.state != 2) {
@@ -781,8 +940,7 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_persistent_kernel(const GemmAr
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this thread's loads of step kt have landed (and its earlier stores)
         __syncthreads();
         if (late && kt + 1 < nk) issue(P, Q, pvo, qvo, iwq, cur.k_len, kt + 1, nxt);
-        const char* p_lds = stg;
-        const char* q_lds = stg + Q_STAGE_OFFSET;
+        const unsigned p_base = (unsigned)(size_t)(lptr_t)stg, q_base = p_base + Q_STAGE_OFFSET;
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 16) {
           if (kk == MOE_EARLY_ISSUE_AT) {
@@ -791,10 +949,10 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_persistent_kernel(const GemmAr
             __builtin_amdgcn_sched_barrier(0);
           }
           bf16x8 pf[PB], qf[2];
-          qf[0] = read_frag<true>(q_lds, qr0, kk, lane);
-          qf[1] = read_frag<true>(q_lds, qr1, kk, lane);
+          qf[0] = read_frag_at<true>(q_off[0], kk, q_base);
+          qf[1] = read_frag_at<true>(q_off[1], kk, q_base);
 #pragma unroll
-          for (int b = 0; b < PB; b++) pf[b] = read_frag<true>(p_lds, wp + 32 * b, kk, lane);
+          for (int b = 0; b < PB; b++) pf[b] = read_frag_at<true>(p_off[b], kk, p_base);
 #pragma unroll
           for (int b = 0; b < PB; b++)
 #pragma unroll
