@@ -77,13 +77,18 @@ constexpr int kCusPerXcd = 32;
 #define MOE_FRAG_PIPELINE_TALL 2
 #endif
 #ifndef MOE_FRAG_PIPELINE_TALL_SWIGLU
-#define MOE_FRAG_PIPELINE_TALL_SWIGLU 0
+#define MOE_FRAG_PIPELINE_TALL_SWIGLU 1
 #endif
 #ifndef MOE_FRAG_PIPELINE_WGRAD
 #define MOE_FRAG_PIPELINE_WGRAD 1
 #endif
+// k offset inside a step at which wavefronts 0..3 request their share of the next stage: half-way through it, or
+// (weight gradients and the SwiGLU forward, where it measured 1-2 % faster; 2 % slower in the others) after three quarters
 #ifndef MOE_EARLY_ISSUE_AT
-#define MOE_EARLY_ISSUE_AT 32   // k offset inside a step at which wavefronts 0..3 request their share of the next stage
+#define MOE_EARLY_ISSUE_AT 32
+#endif
+#ifndef MOE_EARLY_ISSUE_AT_WIDE
+#define MOE_EARLY_ISSUE_AT_WIDE 48
 #endif
 
 enum Epilogue { EPI_BF16 = 0, EPI_SWIGLU = 1, EPI_DSWIGLU = 2, EPI_F32 = 3 };
@@ -470,9 +475,9 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
   // One k-step: wait for stage `cur`, multiply it, and meanwhile fill `nxt` with step kt+1.  The two wavefronts of a
   // SIMD request their share of the next stage at different times of the step (one before its MFMAs, the other
   // between its two halves of them), so that while one is held up issuing loads the other keeps the matrix pipe busy.
-  // (next to a tall tile's 160 accumulator registers the SwiGLU forward, with its two q tensors, has no room for
-  // fragments in flight; a register spilled inside the K loop is ruinous here: its reload waits on the counter that
-  // the direct loads share)
+  // (next to a tall tile's 160 accumulator registers the SwiGLU forward, with its two q tensors, has room for half a
+  // group of fragments in flight only; a register spilled inside the K loop is ruinous here: its reload waits on the
+  // counter that the direct loads share)
   constexpr int FRAG_PIPELINE = (PB == 5) ? (EPI == EPI_SWIGLU ? MOE_FRAG_PIPELINE_TALL_SWIGLU : MOE_FRAG_PIPELINE_TALL)
                                           : (KIND == 0) ? MOE_FRAG_PIPELINE_ROW : MOE_FRAG_PIPELINE_WGRAD;
   // Per-lane LDS offsets of this wavefront's fragments (at kk = 0) from the start of a stage.
@@ -494,8 +499,9 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
     auto rq = [&](int a, int kk) __attribute__((always_inline)) {
       return Q_RC ? read_frag_at<Q_RC>(q_off[a], kk, q_base) : read_frag_at<Q_RC>(q_off[0], kk, q_base + 128u * (NQ == 2 ? 128 : 32) * a);
     };
+    constexpr int EARLY_AT = (KIND == 1 || EPI == EPI_SWIGLU) ? MOE_EARLY_ISSUE_AT_WIDE : MOE_EARLY_ISSUE_AT;
     auto early_issue = [&](int kk) __attribute__((always_inline)) {
-      if (kk == MOE_EARLY_ISSUE_AT) {
+      if (kk == EARLY_AT) {
         __builtin_amdgcn_sched_barrier(0);
         if (!late && kt + 1 < kt_end) issue(kt + 1, nxt);
         __builtin_amdgcn_sched_barrier(0);
