@@ -65,7 +65,7 @@ constexpr int kCusPerXcd = 32;
 #define MOE_SPLIT_PART_STEPS 16
 #endif
 #ifndef MOE_WGRAD_PERSISTENT
-#define MOE_WGRAD_PERSISTENT 1
+#define MOE_WGRAD_PERSISTENT 1   // 0: never, 1: where the generic kernel's grid would be padded, 2: always
 #endif
 // How far ahead of their MFMAs a k-step reads its fragments (0: each group of 16 k reads its own; 1: half a group
 // ahead; 2: rolling, see the k-step): for row tiles of up to 256 rows, for tall row tiles, for the tall row tiles of the
@@ -837,9 +837,9 @@ __global__ __launch_bounds__(NTHREADS) void grouped_gemm_kernel(const GemmArgs A
 // at 300 -- hides behind the previous tile's stores: the next tile's first stage is requested right after the last
 // k-step, into stage 0, while the fp32 results bounce through stage 1 only.  (What it cannot hide: the first k-step's
 // wait counts the stores as well, so it also waits for their acknowledgement, which a block that simply ends leaves to
-// the next block's launch.)  Both operands R-contiguous, ragged K, one fp32 output tensor: the paired gradients
-// dW_gate | dW_up measured 3-8 % slower this way and stay on the kernel above, while dW_down gained up to 22 % (the
-// fine-grained workload's 0.72 -> 0.56 ms) and lost 1-2 % on the Mixtral-shaped one.
+// the next block's launch.)  Both operands R-contiguous, ragged K, one fp32 output tensor or the pair dW_gate | dW_up.
+// Where the generic kernel's grid has no padding this one is 1-4 % slower; where it has, dW_down gained up to 22 % (the
+// fine-grained workload's 0.72 -> 0.56 ms) and the pair 1-5 % (the Zipf shard's 0.92 -> 0.87 ms).
 // ---------------------------------------------------------------------------------------------------------
 struct WgradTile {
   int state;   // 0: nothing to do (padding of the super-tile grid, or no rows to add), 1: a tile, 2: the queue has run out
@@ -847,8 +847,8 @@ struct WgradTile {
   size_t krow0;
 };
 
+template <int NQ>
 __global__ __launch_bounds__(NTHREADS) void wgrad_persistent_kernel(const GemmArgs A) {
-  constexpr int NQ = 1;
   __shared__ __attribute__((aligned(1024))) char stage0[STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) char stage1[STAGE_BYTES];
   __shared__ long long next_ticket;
@@ -894,6 +894,7 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_persistent_kernel(const GemmAr
     P.ld = A.p_ld;
     P.r_valid = t.p_valid;
     Q.base0 = Q.base1 = A.q0 + t.krow0 * A.q_ld + t.q0_col;
+    if (NQ == 2) Q.base1 = A.q1 + t.krow0 * A.q_ld + t.q0_col;
     Q.ld = A.q_ld;
     Q.r_valid = t.q_valid;
     iwq = wave ^ ((t.p_tile_idx & 1) << 2);   // (see ALTERNATE_Q in the kernel above)
@@ -1087,17 +1088,17 @@ static int launch_gemm(const char* label, const GemmArgs& A, long long max_block
   return MOE_OK;
 }
 
-// Weight gradients.  The generic kernel, one block per tile; or, for one output tensor whose tiles do not fill whole
-// 8 x 4 super-tiles (d_ffn or d_model not a multiple of 2048 or 1024: a quarter or a half of the generic kernel's blocks
-// would then be padding that starts, looks up its tile and ends), one persistent block per CU (256) that takes its
-// tiles from a queue per XCD, zeroed by the caller.  Measured: dW_down 0.71 -> 0.57 ms on the fine-grained workload,
-// 0.90 -> 0.86 on the imbalanced one, and 1-2 % slower where there is no padding.
+// Weight gradients.  The generic kernel, one block per tile; or, where the tiles do not fill whole 8 x 4 super-tiles
+// (tiles along p not a multiple of 8 or along q not a multiple of 4: up to half of the generic kernel's blocks would
+// then be padding that starts, looks up its tile and ends), one persistent block per CU (256) that takes its
+// tiles from a queue per XCD, zeroed by the caller.
 template <int NQ>
 static int launch_wgrad(const char* label, const GemmArgs& A, hipStream_t st) {
   if (A.Et <= 0 || A.n_p_tiles <= 0 || A.n_q_tiles <= 0) return MOE_OK;
   const bool padded = (A.n_p_tiles % 8 != 0) || (A.n_q_tiles % 4 != 0);
-  if (NQ == 1 && MOE_WGRAD_PERSISTENT && padded) {
-    MOE_LAUNCH(label, st, wgrad_persistent_kernel, dim3(kNumXcd * kCusPerXcd), dim3(NTHREADS), 0, st, A);
+  // (not the router's launch, which adds the two halves in the epilogue and has 16 tiles per part: 18 -> 32 us this way)
+  if (!A.sum_halves && (MOE_WGRAD_PERSISTENT == 2 || (MOE_WGRAD_PERSISTENT == 1 && padded))) {
+    MOE_LAUNCH(label, st, wgrad_persistent_kernel<NQ>, dim3(kNumXcd * kCusPerXcd), dim3(NTHREADS), 0, st, A);
     return MOE_OK;
   }
   return launch_gemm<1, true, true, NQ, 1, EPI_F32>(label, A, wgrad_blocks(A.Et, A.n_p_tiles, A.n_q_tiles), st);
