@@ -353,10 +353,12 @@ def test_grouped_ffn_fwd_bwd(moe, T, d, f, E, k, Es, dead):
 
 HEIGHT_COUNTS = [1, 31, 33, 64, 65, 128, 129, 256, 257, 300, 320, 321, 0, 577, 512 + 65]
 FEW_COUNTS = [33, 300, 65, 0, 130]
+MANY_TILE_COUNTS = [1300, 70, 0, 1400, 1024 + 30]   # 5 row tiles with a tall last one, 6 with a short last one, 4 with a tall one
 
 
 @pytest.mark.parametrize("d,f,counts", [(128, 256, HEIGHT_COUNTS), (256, 1088, HEIGHT_COUNTS), (3072, 256, HEIGHT_COUNTS),
-                                        (128, 3136, HEIGHT_COUNTS), (3072, 1536, FEW_COUNTS)])
+                                        (128, 3136, HEIGHT_COUNTS), (3072, 1536, FEW_COUNTS),
+                                        (256, 2304, MANY_TILE_COUNTS)])
 def test_grouped_ffn_every_tile_height(moe, d, f, counts):
     """Experts whose row counts hit every height class of a row tile and both sides of every class boundary: 1..64 rows
     (one 32-row block per wavefront), 65..128, 129..256, 257..320 (a full tile that carries up to 64 more rows), 321
@@ -364,8 +366,10 @@ def test_grouped_ffn_every_tile_height(moe, d, f, counts):
     (f = 1088 = 4 * 256 + 64 also puts a 64-wide last column tile on every class.  The last two shapes make few tiles
     with a contraction of 48 k-steps or more, which the kernels then cut along K: d = 3072 in dH, whose arriving part
     applies the d(SwiGLU) epilogue to the summed parts, and f = 3136 = 49 * 64 in the down projection and in dX; the
-    last case, on a few experts, has both dH and dX cut their tiles in one backward call, one after the other on the
-    same arrival counters.)"""
+    fifth case, on a few experts, has both dH and dX cut their tiles in one backward call, one after the other on the
+    same arrival counters.  The last case has experts of more than four row tiles, which the kernels walk column tile by
+    column tile with a tall tile first, next to one of four row tiles, walked in bands of 8 column tiles: f = 2304 is 9
+    column tiles, i.e. a full band and a band of one.)"""
     counts = np.array(counts, dtype=np.int64)
     E, N = counts.size, int(counts.sum())
     offsets = np.zeros(E + 1, dtype=np.int32)
