@@ -24,14 +24,15 @@
 // 32-bit per-lane offset that never changes, so the K loop does no per-lane address arithmetic.  The two wavefronts
 // that share a SIMD request their parts of the next stage at different times of a step (one right after the
 // barrier, the other half-way through its MFMAs): a wavefront is held up while its loads are accepted, and this way
-// its partner has MFMAs to issue meanwhile.  The LDS destination of a direct load is fixed by the lane id, so bank
+// its partner has MFMAs to issue meanwhile; fragment reads run ahead of their MFMAs so that the partner, alone on
+// the matrix pipe, does not stall on LDS latency.  The LDS destination of a direct load is fixed by the lane id, so bank
 // conflicts are avoided by choosing WHICH 16-byte chunk each lane fetches (an XOR swizzle of the chunk index with
 // row bits), and the fragment reads apply the same swizzle.  Every request is a whole 128-byte line (KC) or four of
 // them (RC): the vector L1 handles about one line per two cycles whatever part of it is used.  Rows past the end of
 // a ragged K (weight gradients) are fetched from a zeroed page.  Row tiles of the ragged dimension come from a
 // device-built schedule (no host sync on the counts); the block-id -> tile map deals groups of 32 consecutive tiles
 // (super-tiles of 8 x 4 tiles for the weight gradients) round-robin to the XCDs, so that tiles sharing a panel meet in
-// one L2 and every XCD gets the same mix of experts.
+// one L2 and every XCD gets the same mix of experts; inside a group the tiles that take longest come first.
 #include "common.h"
 
 #include <algorithm>
