@@ -927,9 +927,22 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_persistent_kernel(const GemmAr
 
   WgradTile cur = decode(blockIdx.x / kNumXcd);   // the first tile of a block is its own index in its XCD
   bool first_stage_requested = false;
+  // Whether the stores of the previous tile's epilogue were exactly 32 instructions per wavefront, issued
+  // after the first stage's loads and with no other vector-memory instruction between them and the first k-step's wait.
+  bool stores_behind_loads = false;
+  // (32 = 4 p blocks x 8 row groups of one tensor, or x 4 row groups x 2 tensors)
   while (cur.state != 2) {
-    // the next ticket is drawn now and read after the k-steps
-    if (tid == 0) next_ticket = kCusPerXcd + (long long)atomicAdd(A.queue + xcd, 1);
+    // The ticket for the next tile is drawn now and not looked at before the k-steps are done: whoever needs the
+    // value of an atomic waits for everything the wavefront has in flight, which here would be the previous tile's
+    // stores and this tile's first stage.
+    int my_draw;   // (thread 0 only; left undefined elsewhere on purpose: a defined value would be merged in, i.e. waited for, right here)
+    if (tid == 0) {
+      // (an address the compiler cannot prove wave-uniform: for a uniform one it rewrites the atomic into "one lane adds
+      // the number of active lanes, the others derive theirs", which reads the result at once)
+      int zero = 0;
+      asm volatile("" : "+v"(zero));
+      my_draw = atomicAdd(A.queue + xcd + zero, 1);
+    }
     f32x16 acc[2][PB];
     if (cur.state == 1) {
       TileOperand P, Q;
@@ -944,8 +957,12 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_persistent_kernel(const GemmAr
         for (int b = 0; b < PB; b++)
 #pragma unroll
           for (int v = 0; v < 16; v++) acc[a][b][v] = 0.f;
-      auto k_step = [&](const char* stg, char* nxt, int kt) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this thread's loads of step kt have landed (and its earlier stores)
+      auto k_step = [&](auto first_c, const char* stg, char* nxt, int kt) {
+        // This thread's loads of step kt have landed.  The counter is in issue order, loads and stores alike: the first
+        // stage was requested before the previous tile's stores, so after a full tile's epilogue "all but the
+        // youngest 32" means the loads, and the stores drain while the tile's first step multiplies.
+        if (decltype(first_c)::value && stores_behind_loads) __builtin_amdgcn_s_waitcnt(0x8F70);  // vmcnt(32)
+        else __builtin_amdgcn_s_waitcnt(0x0F70);                                                   // vmcnt(0)
         __syncthreads();
         if (late && kt + 1 < nk) issue(P, Q, pvo, qvo, iwq, cur.k_len, kt + 1, nxt);
         const unsigned p_base = (unsigned)(size_t)(lptr_t)stg, q_base = p_base + Q_STAGE_OFFSET;
@@ -968,11 +985,14 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_persistent_kernel(const GemmAr
               acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[a], pf[b], acc[a][b], 0, 0, 0);
         }
       };
-      for (int kt = 0; kt < nk; kt += 2) {
-        k_step(stage0, stage1, kt);
-        if (kt + 1 < nk) k_step(stage1, stage0, kt + 1);
+      if (nk > 0) k_step(std::true_type{}, stage0, stage1, 0);
+      for (int kt = 1; kt < nk; kt += 2) {
+        k_step(std::false_type{}, stage1, stage0, kt);
+        if (kt + 1 < nk) k_step(std::false_type{}, stage0, stage1, kt + 1);
       }
     }
+    asm volatile("" : "+v"(my_draw));   // (nothing that needs the drawn value may move up across the k-steps)
+    if (tid == 0) next_ticket = kCusPerXcd + (long long)my_draw;
     __syncthreads();   // every wavefront has finished reading the stages; the next ticket is visible
     const long long drawn = next_ticket;   // (the same for every lane: said so, which keeps the tile's description in scalar registers)
     const WgradTile nxt = decode(((long long)__builtin_amdgcn_readfirstlane((int)(drawn >> 32)) << 32) |
@@ -988,24 +1008,28 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_persistent_kernel(const GemmAr
     }
     if (cur.state == 1) {
       // ---- epilogue (see the kernel above): 32 rows at a time through this wavefront's patch of stage 1
+      // (the lane index as this part sees it: opaque, so that its address arithmetic is redone per tile instead of
+      // being held in registers across the K loops)
+      int elane = lane;
+      asm volatile("" : "+v"(elane));
 #pragma unroll
       for (int b = 0; b < PB; b++) {
 #pragma unroll
         for (int a = 0; a < 2; a++)
 #pragma unroll
           for (int v4 = 0; v4 < 4; v4++) {
-            const int q = (NQ == 2 ? 0 : 32 * a) + 8 * v4 + 4 * (lane >> 5);
+            const int q = (NQ == 2 ? 0 : 32 * a) + 8 * v4 + 4 * (elane >> 5);
             float4 r = make_float4(acc[a][b][4 * v4], acc[a][b][4 * v4 + 1], acc[a][b][4 * v4 + 2], acc[a][b][4 * v4 + 3]);
-            *reinterpret_cast<float4*>(wlds + (NQ == 2 ? a * (32 * PITCH) : 0) + (lane & 31) * PITCH + q * 4) = r;
+            *reinterpret_cast<float4*>(wlds + (NQ == 2 ? a * (32 * PITCH) : 0) + (elane & 31) * PITCH + q * 4) = r;
           }
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wavefront's own LDS writes are done
         __builtin_amdgcn_wave_barrier();
-        constexpr int LPR = W / 4;          // lanes per row (4 q = 16 bytes of fp32 per lane)
+        constexpr int LPR = W / 4;          // lanes per row (4 q = 16 bytes of fp32 per elane)
         constexpr int RPI = 64 / LPR;       // rows per instruction
 #pragma unroll
         for (int it = 0; it < 32 / RPI; it++) {
-          const int r = it * RPI + lane / LPR;
-          const int q = (lane % LPR) * 4;
+          const int r = it * RPI + elane / LPR;
+          const int q = (elane % LPR) * 4;
           const int p = wp + 32 * b + r;
           if (p < cur.p_valid && q_base + q < cur.q_valid) {
             const size_t o = (size_t)cur.expert * A.f_expert_stride + (size_t)(cur.p_row0 + p) * A.c_ld + cur.q0_col + q_base + q;
@@ -1025,6 +1049,7 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_persistent_kernel(const GemmAr
         __builtin_amdgcn_wave_barrier();
       }
     }
+    stores_behind_loads = first_stage_requested && cur.state == 1 && !A.accumulate && cur.p_valid == TILE && cur.q_valid == TQ;
     __syncthreads();   // (the ticket slot may be rewritten)
     cur = nxt;
   }
